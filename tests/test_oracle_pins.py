@@ -1,0 +1,378 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests needs a GPU.  Each pin is chosen so that a plausible
+mistake in the oracle (dropped term, wrong sign, transposed axis, wrong tie
+rule) fails it.  The paper prints no worked numeric example of the quantiser,
+the scores or the attention output; the fixtures under tests/golden/ are hand
+derivations from its equations and the size column of its Table 1.
+"""
+import os
+
+import numpy as np
+import pytest
+from scipy.special import softmax
+
+from paper_2503_16163_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append([float(t) for t in line.split()])
+    return out
+
+
+# ---------------------------------------------------------------- widening
+
+@pytest.mark.parametrize("dtype", [synth.FP16, synth.BF16])
+def test_widen_all_patterns(oracle, dtype):
+    """Every finite 16-bit pattern widens to the value numpy gives (library routine)."""
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)[::7]
+    ref = synth.from_bits(bits, dtype)
+    got = oracle.widen(bits, dtype)
+    finite = np.isfinite(ref)
+    assert np.array_equal(got[finite], ref[finite])
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+
+
+# ---------------------------------------------------------------- Eq. 3 (P1)
+
+def test_eq3_intervals_golden(oracle):
+    for mn, mx, x, code, level in _rows("eq3_one_bit_intervals.txt"):
+        grp = np.full(32, mn, np.float32)
+        grp[1], grp[2] = mx, x
+        codes, gmn, gmx, s, z = oracle.quantize_group(grp, 1)
+        assert (gmn, gmx) == (mn, mx)
+        assert codes[2] == code, (mn, mx, x)
+        assert float(codes[2]) * float(s) + float(z) == level
+
+
+@pytest.mark.parametrize("dtype", [synth.FP16, synth.BF16])
+def test_eq3_two_levels_only(oracle, dtype):
+    """Every 1-bit dequantised value is the quarter point or the three-quarter point."""
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        x = synth.from_bits(synth.to_bits(rng.normal(size=32) * rng.choice([0.01, 1, 50]), dtype), dtype)
+        codes, mn, mx, s, z = oracle.quantize_group(x, 1)
+        assert set(np.unique(codes)) <= {0, 1}
+        lo, hi = (3 * float(mn) + float(mx)) / 4, (float(mn) + 3 * float(mx)) / 4
+        deq = codes.astype(np.float64) * float(s) + float(z)
+        want = np.where(codes == 0, lo, hi)
+        assert np.allclose(deq, want, rtol=0, atol=4 * np.spacing(np.float32(max(abs(mn), abs(mx)))))
+        mid = (float(mn) + float(mx)) / 2
+        slack = 2 * np.spacing(np.float32(max(abs(mn), abs(mx), 1e-30)))
+        assert np.all(codes[x < mid - slack] == 0)
+        assert np.all(codes[x > mid + slack] == 1)
+
+
+# ---------------------------------------------------------------- Eq. 2 (P2)
+
+def test_eq2_levels_golden(oracle):
+    for mn, mx, x, code, level in _rows("eq2_two_bit_levels.txt"):
+        grp = np.full(32, mn, np.float32)
+        grp[5], grp[9] = mx, x
+        codes, gmn, gmx, s, z = oracle.quantize_group(grp, 2)
+        assert float(z) == mn and float(s) == (mx - mn) / 3
+        assert codes[9] == code, (mn, mx, x)
+        assert codes[0] == 0 and codes[5] == 3
+        assert float(codes[9]) * float(s) + float(z) == level
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_eq2_nearest_level_bruteforce(oracle, bits):
+    """The chosen code is the nearest of the 2^B levels min + j*s (brute force over j)."""
+    rng = np.random.default_rng(11)
+    top = (1 << bits) - 1
+    for _ in range(300):
+        x = synth.from_bits(synth.to_bits(rng.normal(size=32) * rng.choice([0.1, 1, 30]), synth.FP16), synth.FP16)
+        codes, mn, mx, s, z = oracle.quantize_group(x, bits)
+        assert float(z) == float(mn)
+        assert abs(float(s) - (float(mx) - float(mn)) / top) <= 2 * np.spacing(np.float32(s))
+        levels = float(mn) + np.arange(top + 1) * float(s)
+        dist = np.abs(x.astype(np.float64)[:, None] - levels[None, :])
+        best = dist.min(axis=1)
+        chosen = dist[np.arange(32), codes]
+        assert np.all(chosen <= best + 4 * np.spacing(np.float32(max(abs(mn), abs(mx)))))
+        assert codes[np.argmin(x)] == 0 and codes[np.argmax(x)] == top
+
+
+def test_constant_group(oracle):
+    for bits in (1, 2):
+        codes, mn, mx, s, z = oracle.quantize_group(np.full(64, -2.5, np.float32), bits)
+        assert np.all(codes == 0) and float(s) == 0.0 and float(z) == -2.5
+
+
+# ---------------------------------------------------------------- packing
+
+def test_canonical_packing(oracle):
+    assert oracle.pack_group(np.array([1, 2, 3, 0], np.uint8), 2).tolist() == [0b00111001]
+    assert oracle.pack_group(np.array([1, 0, 0, 0, 0, 0, 0, 1, 0, 1, 0, 0, 0, 0, 0, 0], np.uint8), 1).tolist() == [0x81, 0x02]
+    rng = np.random.default_rng(5)
+    for bits in (1, 2):
+        c = rng.integers(0, 1 << bits, size=64).astype(np.uint8)
+        assert np.array_equal(oracle.unpack_group(oracle.pack_group(c, bits), 64, bits), c)
+
+
+# ---------------------------------------------------------------- Table 1 size column (P3)
+
+def test_table1_cache_size_ratio(oracle):
+    """Codes plus one 16-bit (min,max) pair per group reproduce the printed size ratios."""
+    D = 128
+    for bits, g, printed in _rows("table1_cache_size.txt"):
+        bits, g = int(bits), int(g)
+        S = 4 * g
+        k, v = synth.make_kv(7, 1, 1, S + g, D, synth.FP16)
+        c = oracle.Cache(D, bits, g, g, synth.FP16)
+        c.append(k[0, 0], v[0, 0])
+        e = c.export()
+        nq = c.counts()[1]
+        assert nq > 0
+        total_bits = 0
+        for name in ("k", "v"):
+            total_bits += e[name + "_codes"].size * bits + e[name + "_mnmx"].size * 16
+        ratio = total_bits / (2 * nq * D * 16)
+        # Section 4.1: 128 tokens stay 16-bit in VRAM (64 residual + 64 prefetched, same as
+        # KIVI's 128 residual); at the 32k context the column is quoted on they add 128/32768.
+        assert round(ratio + 128 / 32768, 2) == printed, (bits, g, ratio, printed)
+
+
+# ---------------------------------------------------------------- half step (P4)
+
+@pytest.mark.parametrize("dtype", [synth.FP16, synth.BF16])
+@pytest.mark.parametrize("bits,g", [(2, 32), (2, 64), (1, 32), (1, 64)])
+def test_half_step_bound(oracle, bits, g, dtype):
+    D, S = 128, 4 * g
+    k, v = synth.make_kv(21 + bits + g, 1, 1, S + g, D, dtype)
+    c = oracle.Cache(D, bits, g, g, dtype)
+    c.append(k[0, 0], v[0, 0])
+    n, nq = c.counts()
+    assert nq == n == S + g  # R = g: the ring empties on every flush
+    kd, vd = c.dequant()
+    kh, vh = c.history()
+    e = c.export()
+    assert e["k_codes"].max() <= (1 << bits) - 1 and e["v_codes"].max() <= (1 << bits) - 1
+    ks = np.repeat(e["k_sz"][:, :, 0].astype(np.float64), g, axis=0)          # [Nq, D]
+    vs = np.repeat(e["v_sz"][:, :, 0].astype(np.float64), g, axis=1)          # [Nq, D]
+    kmax = np.repeat(np.abs(e["k_mnmx"]).max(axis=2), g, axis=0)
+    vmax = np.repeat(np.abs(e["v_mnmx"]).max(axis=2), g, axis=1)
+    for deq, full, s, amax in ((kd, kh[:nq], ks, kmax), (vd, vh[:nq], vs, vmax)):
+        bound = s / 2 * (1 + 1e-5) + 4 * np.spacing(amax.astype(np.float32)).astype(np.float64)
+        assert np.all(np.abs(deq - full) <= bound)
+
+
+# ---------------------------------------------------------------- axes, streaming (P5)
+
+@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 32, 64), (2, 64, 64), (2, 32, 96)])
+def test_streaming_equals_per_group(oracle, bits, g, R):
+    """Token-by-token appends give, for every group, what quantising that slice alone gives.
+
+    The slices are cut here with numpy: keys along tokens for one channel,
+    values along channels for one token (KIVI's axes, Section 2.1 / 4.1).
+    """
+    D, S = 128, 3 * R + 7
+    k, v = synth.make_kv(33, 1, 1, S, D, synth.FP16)
+    c = oracle.Cache(D, bits, g, R, synth.FP16)
+    for t in range(S):
+        c.append(k[0, 0, t:t + 1], v[0, 0, t:t + 1])
+        n, nq = c.counts()
+        assert n == t + 1 and nq % g == 0 and 0 <= n - nq < R
+        if n >= R:
+            assert n - nq >= R - g
+    n, nq = c.counts()
+    e = c.export()
+    kf, vf = synth.from_bits(k[0, 0], synth.FP16), synth.from_bits(v[0, 0], synth.FP16)
+    rng = np.random.default_rng(0)
+    for _ in range(60):
+        j, ch = rng.integers(nq // g), rng.integers(D)
+        codes, mn, mx, s, z = oracle.quantize_group(kf[j * g:(j + 1) * g, ch], bits)
+        assert np.array_equal(e["k_codes"][j * g:(j + 1) * g, ch], codes)
+        assert tuple(e["k_mnmx"][j, ch]) == (mn, mx) and tuple(e["k_sz"][j, ch]) == (s, z)
+        t, m = rng.integers(nq), rng.integers(D // g)
+        codes, mn, mx, s, z = oracle.quantize_group(vf[t, m * g:(m + 1) * g], bits)
+        assert np.array_equal(e["v_codes"][t, m * g:(m + 1) * g], codes)
+        assert tuple(e["v_mnmx"][t, m]) == (mn, mx) and tuple(e["v_sz"][t, m]) == (s, z)
+    # one bulk append reaches the same state
+    c2 = oracle.Cache(D, bits, g, R, synth.FP16)
+    c2.append(k[0, 0], v[0, 0])
+    e2 = c2.export()
+    assert c2.counts() == (n, nq)
+    for name in e:
+        assert np.array_equal(e[name], e2[name])
+
+
+def test_grouping_axes_by_error(oracle):
+    """Per-channel key groups absorb a per-channel offset; per-token value groups a per-token one."""
+    D, g, S = 128, 32, 128
+    rng = np.random.default_rng(9)
+    k = rng.normal(size=(S, D)).astype(np.float32) + (np.arange(D) * 8.0)[None, :]
+    v = rng.normal(size=(S, D)).astype(np.float32) + (np.arange(S) * 8.0)[:, None]
+    c = oracle.Cache(D, 2, g, g, synth.FP16)
+    c.append(synth.to_bits(k, synth.FP16), synth.to_bits(v, synth.FP16))
+    kd, vd = c.dequant()
+    kh, vh = c.history()
+    assert np.abs(kd - kh).max() < 1.5 and np.abs(vd - vh).max() < 1.5
+
+
+# ---------------------------------------------------------------- top-k (P8)
+
+def test_topk_against_full_sort(oracle):
+    rng = np.random.default_rng(17)
+    for n, k in ((1, 1), (50, 7), (257, 64), (1000, 1000), (40, 64)):
+        s = rng.normal(size=n)
+        idx = oracle.topk(s, k)
+        keff = min(k, n)
+        want = np.sort(np.argsort(-s, kind="stable")[:keff])
+        assert np.array_equal(idx[:keff], want)
+        assert np.all(idx[keff:] == -1)
+    s = rng.normal(size=300)
+    assert oracle.topk(s, 1)[0] == int(np.argmax(s))
+    assert np.array_equal(oracle.topk(s, 300), np.arange(300))
+
+
+def test_topk_ties_lower_index_first(oracle):
+    s = np.array([1.0, 5.0, 5.0, 5.0, 0.0, 5.0, 7.0])
+    assert oracle.topk(s, 3).tolist() == [1, 2, 6]
+    assert oracle.topk(s, 4).tolist() == [1, 2, 3, 6]
+    assert oracle.topk(np.zeros(10), 4).tolist() == [0, 1, 2, 3]
+
+
+# ---------------------------------------------------------------- scores and attention (P6, P7, P9)
+
+def _setup(oracle, bits=2, g=32, R=64, S=200, G=1, dtype=synth.FP16, seed=41):
+    D = 128
+    k, v = synth.make_kv(seed, 1, 1, S, D, dtype)
+    q = synth.make_queries(seed, 1, G, D, dtype)[0]            # [G, 2, D]
+    ks, vs = synth.make_spec_kv(seed, 1, 1, D, dtype)
+    c = oracle.Cache(D, bits, g, R, dtype)
+    c.append(k[0, 0], v[0, 0])
+    return c, q, ks[0, 0, 0], vs[0, 0, 0]
+
+
+@pytest.mark.parametrize("G", [1, 4])
+def test_scores_are_scaled_q_dot_dequantised_keys(oracle, G):
+    c, q, _, _ = _setup(oracle, G=G, dtype=synth.BF16)
+    sm = 0.11
+    logits, sigma = c.scores(q, sm)
+    kd, _ = c.dequant()
+    qf = synth.from_bits(q, synth.BF16).astype(np.float64)
+    want = sm * np.einsum("grc,nc->grn", qf, kd)
+    assert np.allclose(logits, want, rtol=1e-12, atol=1e-12)
+    assert np.allclose(sigma, want[:, -1, :].max(axis=0), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("bits,g,G", [(2, 32, 1), (1, 32, 4), (2, 64, 2)])
+def test_all_positions_prefetched_is_textbook_attention(oracle, bits, g, G):
+    """Eq. 1 with K = every quantised position: all low-bit pairs are replaced, so the result
+    is ordinary softmax attention over the 16-bit history (computed here with numpy/scipy)."""
+    c, q, ks, vs = _setup(oracle, bits=bits, g=g, G=G, S=203)
+    n, nq = c.counts()
+    sm = 1 / np.sqrt(128)
+    out = c.attend(q, sm, P=np.arange(nq, dtype=np.int32), k_spec=ks, v_spec=vs)
+    kh, vh = c.history()
+    qf = synth.from_bits(q, synth.FP16).astype(np.float64)
+    ksf, vsf = (synth.from_bits(a, synth.FP16).astype(np.float64) for a in (ks, vs))
+    for h in range(G):
+        w0 = softmax(sm * kh @ qf[h, 0])
+        assert np.allclose(out[h, 0], w0 @ vh, rtol=1e-11, atol=1e-12)
+        k1, v1 = np.vstack([kh, ksf]), np.vstack([vh, vsf])
+        w1 = softmax(sm * k1 @ qf[h, 1])
+        assert np.allclose(out[h, 1], w1 @ v1, rtol=1e-11, atol=1e-12)
+    full = c.full_attention(q, sm, k_spec=ks, v_spec=vs)
+    assert np.allclose(out, full, rtol=1e-11, atol=1e-12)
+
+
+@pytest.mark.parametrize("bits,g", [(2, 32), (1, 32), (2, 64)])
+def test_nothing_prefetched_is_low_bit_attention(oracle, bits, g):
+    """Eq. 1 with K empty (the KIVI baseline of Section 4.4): low-bit prefix + 16-bit residual."""
+    c, q, _, _ = _setup(oracle, bits=bits, g=g, S=221)
+    n, nq = c.counts()
+    assert 0 < nq < n
+    sm = 1 / np.sqrt(128)
+    out = c.attend(q, sm)
+    kd, vd = c.dequant()
+    kh, vh = c.history()
+    km, vm = np.vstack([kd, kh[nq:]]), np.vstack([vd, vh[nq:]])
+    qf = synth.from_bits(q, synth.FP16).astype(np.float64)
+    for r in range(2):
+        w = softmax(sm * km @ qf[0, r])
+        assert np.allclose(out[0, r], w @ vm, rtol=1e-11, atol=1e-12)
+
+
+def test_partial_prefetch_replaces_exactly_those_rows(oracle):
+    c, q, ks, vs = _setup(oracle, S=300, G=2)
+    n, nq = c.counts()
+    sm = 1 / np.sqrt(128)
+    P = np.array([3, 17, 64, 65, nq - 1, -1, -1], np.int32)
+    out = c.attend(q, sm, P=P, k_spec=ks, v_spec=vs)
+    kd, vd = c.dequant()
+    kh, vh = c.history()
+    km, vm = np.vstack([kd, kh[nq:]]), np.vstack([vd, vh[nq:]])
+    sel = P[P >= 0]
+    km[sel], vm[sel] = kh[sel], vh[sel]
+    qf = synth.from_bits(q, synth.FP16).astype(np.float64)
+    ksf, vsf = (synth.from_bits(a, synth.FP16).astype(np.float64) for a in (ks, vs))
+    for h in range(2):
+        assert np.allclose(out[h, 0], softmax(sm * km @ qf[h, 0]) @ vm, rtol=1e-11, atol=1e-12)
+        k1, v1 = np.vstack([km, ksf]), np.vstack([vm, vsf])
+        assert np.allclose(out[h, 1], softmax(sm * k1 @ qf[h, 1]) @ v1, rtol=1e-11, atol=1e-12)
+    # the current row must not see the transient pair
+    out_nospec = c.attend(q, sm, P=P)
+    assert np.allclose(out_nospec[:, 0], out[:, 0], rtol=1e-13, atol=0)
+    assert not np.allclose(out_nospec[:, 1], out[:, 1], rtol=1e-6, atol=0)
+
+
+def test_softmax_weights_and_hit_rate(oracle):
+    c, q, _, _ = _setup(oracle, S=180, G=2)
+    n, nq = c.counts()
+    out, w = c.full_attention(q, 0.2, want_weights=True)
+    assert np.all(w >= 0) and np.allclose(w.sum(axis=-1), 1.0, rtol=0, atol=1e-12)
+    assert abs(oracle.hit_rate(w[0, 1], np.arange(n, dtype=np.int32)) - 1.0) < 1e-12
+    top = oracle.topk(w[0, 1], 10)
+    rnd = np.arange(10, dtype=np.int32)
+    assert oracle.hit_rate(w[0, 1], top) >= oracle.hit_rate(w[0, 1], rnd)
+    assert oracle.hit_rate(w[0, 1], np.array([-1, n + 5], np.int32)) == 0.0
+
+
+def test_more_prefetch_recovers_full_attention(oracle):
+    """Diagnostic from Section 4.4: the gap to full attention shrinks as k grows and vanishes at k = Nq."""
+    c, q, _, _ = _setup(oracle, bits=1, S=512 + 32, seed=77)
+    n, nq = c.counts()
+    sm = 1 / np.sqrt(128)
+    full = c.full_attention(q, sm)
+    _, sigma = c.scores(q, sm)
+    errs = []
+    for k in (0, 64, nq):
+        out = c.attend(q, sm, P=oracle.topk(sigma, k) if k else None)
+        errs.append(np.abs(out[0, 1] - full[0, 1]).max())
+    assert errs[1] < errs[0] and errs[2] < 1e-12
+
+
+def test_planted_keys_are_selected(oracle):
+    D, S, g = 128, 512, 32
+    k, v = synth.make_kv(91, 1, 1, S, D, synth.FP16, n_outlier=0)
+    q = synth.make_queries(91, 1, 1, D, synth.FP16)[0]
+    qf = synth.from_bits(q, synth.FP16)
+    kf = synth.from_bits(k, synth.FP16)
+    planted = np.array([5, 100, 101, 333, 470])
+    kf[0, 0, planted] = 4.0 * qf[0, 1]
+    c = oracle.Cache(D, 2, g, g, synth.FP16)
+    c.append(synth.to_bits(kf[0, 0], synth.FP16), v[0, 0])
+    _, sigma = c.scores(q, 1 / np.sqrt(D))
+    assert set(planted) <= set(oracle.topk(sigma, 8).tolist())
+
+
+def test_invalid_arguments_are_errors(oracle):
+    with pytest.raises(ValueError):
+        oracle.Cache(128, 3, 32, 64, 0)
+    with pytest.raises(ValueError):
+        oracle.Cache(128, 2, 48, 96, 0)
+    with pytest.raises(ValueError):
+        oracle.Cache(128, 2, 32, 48, 0)
+    c, q, _, _ = _setup(oracle, S=100)
+    with pytest.raises(RuntimeError):
+        c.attend(q, 0.1, P=np.array([c.counts()[1]], np.int32))
