@@ -1,0 +1,180 @@
+/*
+ * specache.h: C ABI of the MI355X (gfx950) SpeCache decode-step library.
+ *
+ * One attention layer's per-decode-step hot path of SpeCache (arXiv 2503.16163):
+ * quantise and append the new KV pair to the low-bit VRAM copy C' and offload it
+ * to the 16-bit CPU copy C; score the low-bit keys against the current and the
+ * speculative query in one pass; select the top-k positions of the speculative
+ * row; prefetch those 16-bit pairs from pinned host memory on a side stream;
+ * attend over C' with the prefetched pairs substituted (Section 3.3 "Decoding",
+ * Eq. 1; Section 3.4, Eq. 2-3; Appendix A algorithms "Pre-decoding", "Decoding").
+ *
+ * General conventions
+ *   - Every function returns 0 on success or a negative specache_status.  Nothing
+ *     throws, aborts or prints.  specache_last_error() gives a message for the
+ *     most recent failure on that context.
+ *   - "device" pointers are HIP device memory on the context's GPU, "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it passes
+ *     in; the context owns the caches, the pinned host store, the staging slots,
+ *     its scratch memory and its events.
+ *   - Streams are hipStream_t values passed as void* (NULL = the null stream).
+ *     The four hot calls only enqueue work; create / destroy / export_* /
+ *     debug_* synchronise.
+ *   - 16-bit tensors (dtype of the config: binary16 or bfloat16) are contiguous
+ *     with the head dimension innermost.  head_dim is 128.
+ *   - Calls on one context must come from one host thread at a time.
+ *   - A context keeps one score scratch: specache_attend(layer) must follow the
+ *     specache_score_topk of the same layer with no other layer scored between.
+ */
+#ifndef SPECACHE_H
+#define SPECACHE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum specache_status {
+    SPECACHE_OK = 0,
+    SPECACHE_EINVAL = -1,    /* bad argument or configuration                         */
+    SPECACHE_ECAPACITY = -2, /* append would exceed max_seq                           */
+    SPECACHE_ENOMEM = -3,    /* device or pinned host allocation failed               */
+    SPECACHE_EHIP = -4,      /* a HIP runtime call failed                             */
+    SPECACHE_ESTATE = -5     /* call order violated (slot never gathered, layer
+                                mismatch between score_topk and attend, empty cache) */
+} specache_status;
+
+enum { SPECACHE_FP16 = 0, SPECACHE_BF16 = 1 };
+
+/*
+ * Configuration (Section 4.1 "Implementation Details" names the knobs: bit width,
+ * group size, residual length, k).  All fields are validated by specache_create.
+ */
+typedef struct specache_config {
+    int32_t n_layers;   /* >= 1                                                        */
+    int32_t batch;      /* B >= 1                                                      */
+    int32_t n_q_heads;  /* Hq, a multiple of n_kv_heads; Hq / Hkv in {1, 2, 4, 8}      */
+    int32_t n_kv_heads; /* Hkv >= 1                                                    */
+    int32_t head_dim;   /* must be 128                                                 */
+    int32_t bits;       /* 1 (Eq. 3) or 2 (Eq. 2)                                      */
+    int32_t group;      /* g: 32 or 64; keys grouped per channel over g tokens, values
+                           per token over g channels                                   */
+    int32_t residual;   /* R: multiple of g, g <= R <= 256.  Tokens are appended one at
+                           a time; when N - Nq reaches R the oldest g unquantised
+                           tokens are quantised.  The paper uses 64.                   */
+    int32_t max_seq;    /* capacity in tokens per (batch, KV head), multiple of 64     */
+    int32_t topk;       /* k: 1 .. 4096                                                */
+    int32_t dtype;      /* SPECACHE_FP16 or SPECACHE_BF16: type of K, V, q and C       */
+    float sm_scale;     /* logit scale; <= 0 selects 1/sqrt(head_dim)                  */
+} specache_config;
+
+typedef struct specache_ctx specache_ctx;
+
+/* Allocates every buffer for all layers on the current HIP device (including
+ * n_layers * B * Hkv * max_seq * 512 bytes of pinned host memory for C).
+ * *out is NULL on failure. */
+int specache_create(const specache_config* cfg, specache_ctx** out);
+
+/* Synchronises the device and frees everything.  NULL is allowed. */
+int specache_destroy(specache_ctx* ctx);
+
+/* Message of the most recent failed call on ctx (never NULL; "" if none).
+ * With ctx == NULL returns the message of the last failed specache_create. */
+const char* specache_last_error(const specache_ctx* ctx);
+
+/* Token counts of a layer: N tokens cached, of which the first Nq are quantised
+ * (Nq is a multiple of g; N - Nq < R tokens sit 16-bit in the VRAM residual). */
+int specache_counts(const specache_ctx* ctx, int32_t layer, int32_t* n_tokens, int32_t* n_quantized);
+
+/* Host-only helper, no GPU work: how many groups of g tokens an append of n_new
+ * tokens moves from the residual into C' under the residual policy above, for a
+ * layer holding n_tokens of which n_quantized are quantised.
+ * Errors: EINVAL (inconsistent counts, null output). */
+int specache_plan_append(int32_t residual, int32_t group, int32_t n_tokens, int32_t n_quantized, int32_t n_new,
+                         int32_t* n_flush_groups);
+
+/*
+ * Quant + Offload of new KV pairs (Appendix A "Decoding": C' = [C', Quant(K_t, V_t)],
+ * C = [C, Offload(C_t)]; quantiser of Eq. 2 for 2 bits, Eq. 3 for 1 bit).
+ * k_new, v_new: device, 16-bit, [B, Hkv, n_new, 128].  Defined as n_new single-token
+ * appends in order (n_new = the prompt length performs the bulk load after
+ * prefill).  Every token is written to the pinned host store and to the VRAM
+ * residual; full groups leaving the residual are quantised and packed.
+ * Errors: EINVAL (null pointer, n_new < 0, bad layer), ECAPACITY (N + n_new >
+ * max_seq; nothing is appended).
+ */
+int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new,
+                             int32_t n_new, void* stream);
+
+/*
+ * Low-bit scoring and ArgTopK (Appendix A "Decoding": A = Softmax(Q K^T) on the
+ * low-bit keys, K_{t+1} = ArgTopK(A_{1,:}); "Pre-decoding" with n_rows = 1).
+ * q: device, 16-bit, [B, Hq, n_rows, 128], n_rows in {1, 2}; row 0 is the output
+ * token's query, row 1 the speculative token's.  For every quantised position
+ * i < Nq and every query head the logit sm_scale * q . K'_i is computed from the
+ * packed keys (read once for all rows and heads of a KV head) and kept in the
+ * context for the following specache_attend.  The selection score of position i
+ * for a KV head is the maximum over its Hq/Hkv query heads of the LAST row's
+ * logit.  topk_idx_out: device int32 [B, Hkv, k]; receives the min(k, Nq)
+ * positions with the largest selection score (ties to the lower index) in
+ * ascending index order, the rest -1.
+ * Errors: EINVAL, ESTATE (no call order requirement fails here; Nq = 0 is
+ * allowed and yields all -1).
+ */
+int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows,
+                        int32_t* topk_idx_out, void* stream);
+
+/*
+ * Pre-fetch(C_K) (Section 3.3: the selected 16-bit pairs are fetched from CPU
+ * memory in parallel with later computation).  idx: device int32 [B, Hkv, k],
+ * ascending with -1 padding (the format specache_score_topk writes).  Copies
+ * the selected (K, V) rows from the pinned host store into staging slot
+ * `slot` (0 or 1) of the layer, together with the index list.  Enqueued on
+ * side_stream; the library orders it after the specache_score_topk that wrote
+ * idx and after the last specache_attend that read this slot, and orders later
+ * specache_attend calls on this slot after it, with events of its own.
+ * Reusing a slot discards what it held (the paper's eviction).
+ * Errors: EINVAL (slot not 0/1, null idx, bad layer).
+ */
+int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_t slot, void* side_stream);
+
+/*
+ * Mixed attention, Eq. 1: O = Attn([T_t, T'_{t+1}], C' u C_K).
+ * q as in specache_score_topk (same n_rows).  Candidates of every row: quantised
+ * positions i < Nq with the staged 16-bit pair where i is in the slot's index
+ * list and the dequantised low-bit pair elsewhere; the 16-bit residual positions
+ * Nq <= i < N; and, for the last row only when k_spec/v_spec are non-NULL
+ * (device, 16-bit, [B, Hkv, 1, 128]), that transient pair (it is never appended).
+ * slot = -1: nothing prefetched (pre-decoding, or the k = 0 baseline).
+ * out: device float32 [B, Hq, n_rows, 128].
+ * Errors: EINVAL; ESTATE (slot never gathered, layer not the last one scored,
+ * n_rows differs from the scoring call, the cache grew since the scoring call,
+ * or no candidate at all).
+ */
+int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                    const void* v_spec, int32_t slot, float* out, void* stream);
+
+/*
+ * Parity hooks (synchronise the device; all output pointers are host memory and
+ * may be NULL to skip that array).
+ *
+ * specache_export_quantized: canonical view of C' of one layer.
+ *   k_codes u8 [B,Hkv,Nq,128]      one code per byte
+ *   k_minmax u16 [B,Hkv,Nq/g,128,2] stored (min,max) bit patterns per key group
+ *   k_scale_zero f32 [B,Hkv,Nq/g,128,2] (s,z) as the kernels derive them on the GPU
+ *   v_codes u8 [B,Hkv,Nq,128], v_minmax u16 [B,Hkv,Nq,128/g,2], v_scale_zero f32 [...,2]
+ * specache_export_rows: 16-bit rows [first, first+count) of the host store C,
+ *   out u16 [B,Hkv,count,2,128] (K row then V row per token).
+ * specache_debug_logits: the logits kept by the last specache_score_topk,
+ *   out f32 [B,Hq,n_rows,Nq].
+ */
+int specache_export_quantized(specache_ctx* ctx, int32_t layer, uint8_t* k_codes, uint16_t* k_minmax,
+                              float* k_scale_zero, uint8_t* v_codes, uint16_t* v_minmax, float* v_scale_zero);
+int specache_export_rows(specache_ctx* ctx, int32_t layer, int32_t first, int32_t count, uint16_t* out);
+int specache_debug_logits(specache_ctx* ctx, float* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECACHE_H */

@@ -1,0 +1,161 @@
+"""Thin ctypes binding of libspecache.so: argument marshalling only.
+
+Every step of the decode path runs in the HIP kernels behind the C ABI declared
+in include/specache.h; the functions here carry the same names.  Tensors are
+PyTorch tensors on the GPU (PyTorch provides device memory and streams) or raw
+integer device addresses.  There is no CPU fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+import ctypes as C
+import os
+
+from . import build as _build
+
+FP16, BF16 = 0, 1
+OK, EINVAL, ECAPACITY, ENOMEM, EHIP, ESTATE = 0, -1, -2, -3, -4, -5
+_NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHIP", ESTATE: "ESTATE"}
+
+EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
+           "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
+           "specache_attend", "specache_export_quantized", "specache_export_rows", "specache_debug_logits"]
+
+
+class Config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "bits",
+                                         "group", "residual", "max_seq", "topk", "dtype")] + [("sm_scale", C.c_float)]
+
+
+class SpeCacheError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"specache: {_NAMES.get(code, code)}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libspecache.so (building it first only if it was never built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = C.CDLL(_build.LIB)
+        vp, i32 = C.c_void_p, C.c_int32
+        L.specache_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
+        L.specache_destroy.argtypes = [vp]
+        L.specache_last_error.argtypes = [vp]
+        L.specache_last_error.restype = C.c_char_p
+        L.specache_counts.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32)]
+        L.specache_plan_append.argtypes = [i32, i32, i32, i32, i32, C.POINTER(i32)]
+        L.specache_quantize_append.argtypes = [vp, i32, vp, vp, i32, vp]
+        L.specache_score_topk.argtypes = [vp, i32, vp, i32, vp, vp]
+        L.specache_gather.argtypes = [vp, i32, vp, i32, vp]
+        L.specache_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
+        L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
+        L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
+        L.specache_debug_logits.argtypes = [vp, vp]
+        for name in EXPORTS:
+            if name != "specache_last_error":
+                getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _ptr(x):
+    """Device (or host) address of a tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return x.ctypes.data
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream  # torch.cuda.Stream
+
+
+def plan_append(residual, group, n_tokens, n_quantized, n_new):
+    out = C.c_int32()
+    rc = lib().specache_plan_append(residual, group, n_tokens, n_quantized, n_new, C.byref(out))
+    if rc != OK:
+        raise SpeCacheError(rc, "plan_append: inconsistent arguments")
+    return out.value
+
+
+class SpeCache:
+    """Owner of a specache_ctx; methods mirror the C calls one to one."""
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, bits, group, max_seq, topk, dtype,
+                 residual=64, head_dim=128, sm_scale=0.0):
+        self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, bits, group, residual, max_seq,
+                          topk, dtype, sm_scale)
+        self._ctx = C.c_void_p()
+        rc = lib().specache_create(C.byref(self.cfg), C.byref(self._ctx))
+        if rc != OK:
+            raise SpeCacheError(rc, lib().specache_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_ctx", None):
+            lib().specache_destroy(self._ctx)
+            self._ctx = None
+
+    def __del__(self):
+        self.close()
+
+    def _check(self, rc):
+        if rc != OK:
+            raise SpeCacheError(rc, lib().specache_last_error(self._ctx).decode())
+
+    def counts(self, layer):
+        n, nq = C.c_int32(), C.c_int32()
+        self._check(lib().specache_counts(self._ctx, layer, C.byref(n), C.byref(nq)))
+        return n.value, nq.value
+
+    def quantize_append(self, layer, k_new, v_new, n_new, stream=None):
+        self._check(lib().specache_quantize_append(self._ctx, layer, _ptr(k_new), _ptr(v_new), n_new, _stream(stream)))
+
+    def score_topk(self, layer, q, n_rows, topk_idx_out, stream=None):
+        self._check(lib().specache_score_topk(self._ctx, layer, _ptr(q), n_rows, _ptr(topk_idx_out), _stream(stream)))
+
+    def gather(self, layer, idx, slot, side_stream=None):
+        self._check(lib().specache_gather(self._ctx, layer, _ptr(idx), slot, _stream(side_stream)))
+
+    def attend(self, layer, q, n_rows, k_spec, v_spec, slot, out, stream=None):
+        self._check(lib().specache_attend(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
+                                          _ptr(out), _stream(stream)))
+
+    # ---- parity hooks (host numpy arrays) ------------------------------------
+    def export_quantized(self, layer):
+        import numpy as np
+        c = self.cfg
+        rows, (_, nq), g, D = c.batch * c.n_kv_heads, self.counts(layer), c.group, c.head_dim
+        shp = (c.batch, c.n_kv_heads)
+        r = dict(k_codes=np.zeros(shp + (nq, D), np.uint8), k_mnmx=np.zeros(shp + (nq // g, D, 2), np.uint16),
+                 k_sz=np.zeros(shp + (nq // g, D, 2), np.float32), v_codes=np.zeros(shp + (nq, D), np.uint8),
+                 v_mnmx=np.zeros(shp + (nq, D // g, 2), np.uint16), v_sz=np.zeros(shp + (nq, D // g, 2), np.float32))
+        self._check(lib().specache_export_quantized(self._ctx, layer, _ptr(r["k_codes"]), _ptr(r["k_mnmx"]),
+                                                    _ptr(r["k_sz"]), _ptr(r["v_codes"]), _ptr(r["v_mnmx"]),
+                                                    _ptr(r["v_sz"])))
+        return r
+
+    def export_rows(self, layer, first, count):
+        import numpy as np
+        c = self.cfg
+        out = np.zeros((c.batch, c.n_kv_heads, count, 2, c.head_dim), np.uint16)
+        self._check(lib().specache_export_rows(self._ctx, layer, first, count, _ptr(out)))
+        return out
+
+    def debug_logits(self, layer, n_rows):
+        import numpy as np
+        c = self.cfg
+        _, nq = self.counts(layer)
+        out = np.zeros((c.batch, c.n_q_heads, n_rows, nq), np.float32)
+        self._check(lib().specache_debug_logits(self._ctx, _ptr(out)))
+        return out

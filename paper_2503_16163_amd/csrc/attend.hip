@@ -1,0 +1,465 @@
+// Mixed attention of Eq. 1 (Section 3.3): Attn([T_t, T'_{t+1}], C' u C_K).
+//
+// Candidates of a query row: quantised positions i < Nq (the prefetched 16-bit
+// pair where i is in the slot's index list, the dequantised low-bit pair
+// elsewhere), the 16-bit residual positions, and for the speculative row its own
+// transient pair.  The low-bit logits were kept by the scoring pass.
+//
+// Split over the sequence: "main" workgroups take chunks of quantised positions,
+// "extra" workgroups take the 16-bit candidates (staged pairs, residual, transient
+// pair); each writes an un-normalised partial (max, sum, sum p*V) and a combine
+// kernel merges them with the usual log-sum-exp rescaling.  Prefetched positions
+// are removed from the main chunks by setting their logit to -inf in LDS; the
+// staged pair then enters through the extra chunks, which is Eq. 1's "replace".
+//
+// Values are quantised per token over g channels, so for the main chunks
+//   sum_i p_i V'[i][c] = sum_i (p_i s[i][m]) code[i][c] + sum_i p_i z[i][m],  m = c / g.
+// A lane owns 8/BITS channels and reads 16 tokens of them as one 16-byte load;
+// p_i s[i][m] comes from LDS (computed once per token by the softmax phase).
+#include "kernels.h"
+#include "layout.h"
+
+namespace specache {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kExtraChunk = 128;
+
+__host__ __device__ constexpr int main_chunk(int NR) { return NR <= 4 ? 512 : NR <= 8 ? 256 : 128; }
+
+template <int B>
+__device__ __forceinline__ float cvt_ubyte(uint32_t w) {
+    float f;
+    if constexpr (B == 0) asm("v_cvt_f32_ubyte0 %0, %1" : "=v"(f) : "v"(w));
+    if constexpr (B == 1) asm("v_cvt_f32_ubyte1 %0, %1" : "=v"(f) : "v"(w));
+    if constexpr (B == 2) asm("v_cvt_f32_ubyte2 %0, %1" : "=v"(f) : "v"(w));
+    if constexpr (B == 3) asm("v_cvt_f32_ubyte3 %0, %1" : "=v"(f) : "v"(w));
+    return f;
+}
+
+__device__ __forceinline__ uint32_t comp(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+struct AttendArgs {
+    const uint16_t* q;         // [rows*NR][128]
+    const float* logits;       // [rows*NR][logit_stride]
+    size_t logit_stride;
+    const uint16_t* slot;      // [rows][k][256] or null
+    const int32_t* slot_idx;   // [rows][k] or null
+    const uint16_t* k_spec;    // [rows][128] or null
+    const uint16_t* v_spec;
+    float* part_o;             // [rows][max_chunks][NR][128]
+    float* part_ml;            // [rows][max_chunks][NR][2]
+    int max_chunks, n_main, N, Nq;
+    float sm_scale;
+};
+
+// Softmax numerators of one chunk held in lg[NR][CH]: on return lg holds
+// p = exp(l - m); m_out/l_out hold the chunk max and sum of every row.
+template <int NR, int CH>
+__device__ __forceinline__ void chunk_softmax(float (*lg)[CH], int n, float* red, float* m_out, float* l_out) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float mloc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) mloc[r] = -INFINITY;
+    for (int i = tid; i < n; i += kThreads)
+#pragma unroll
+        for (int r = 0; r < NR; ++r) mloc[r] = fmaxf(mloc[r], lg[r][i]);
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const float v = wave_max(mloc[r]);
+        if (lane == 0) red[wave * NR + r] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        float v = red[r];
+        for (int w = 1; w < kWaves; ++w) v = fmaxf(v, red[w * NR + r]);
+        m_out[r] = v;
+    }
+    __syncthreads();
+    float sloc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) sloc[r] = 0.0f;
+    for (int i = tid; i < n; i += kThreads)
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const float ms = m_out[r] == -INFINITY ? 0.0f : m_out[r];
+            const float p = __expf(lg[r][i] - ms);
+            lg[r][i] = p;
+            sloc[r] += p;
+        }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const float v = wave_sum(sloc[r]);
+        if (lane == 0) red[wave * NR + r] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        float v = red[r];
+        for (int w = 1; w < kWaves; ++w) v += red[w * NR + r];
+        l_out[r] = v;
+    }
+    __syncthreads();
+}
+
+template <int BITS, int GROUP, int G, int NROWS, bool BF16>
+__global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, AttendArgs A) {
+    constexpr int NR = G * NROWS;
+    constexpr int CH = main_chunk(NR);
+    constexpr int M = kD / GROUP;            // value groups per token
+    constexpr int CPB = 8 / BITS;            // channels per code byte (per lane)
+    constexpr int LPB = 32 * BITS;           // lanes per 32-token block
+    constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
+    constexpr int CHX = CH > kExtraChunk ? CH : kExtraChunk;
+    // region A: lg[NR][CHX] then ps[M][CH][NR]; reused as o_lds[kWaves][NR][128] at the end
+    constexpr int kLg = NR * CHX, kPs = M * CH * NR, kOl = kWaves * NR * kD;
+    constexpr int kRegion = (kLg + kPs) > kOl ? (kLg + kPs) : kOl;
+    __shared__ __attribute__((aligned(16))) float smem[kRegion];
+    __shared__ float red[kWaves * NR * (1 + M)];
+    __shared__ float qf[NR][kD];
+
+    float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
+    float* ps = smem + kLg;                  // [M][CH][NR]
+    float* o_lds = smem;                     // [kWaves][NR][128]
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int row = blockIdx.y, chunk = blockIdx.x;
+    float m_row[NR], l_row[NR];
+    float* po = A.part_o + (((size_t)row * A.max_chunks + chunk) * NR) * kD;
+    float* pml = A.part_ml + (((size_t)row * A.max_chunks + chunk) * NR) * 2;
+
+    if (chunk < A.n_main) {
+        // ------------------------------------------------------------ quantised positions
+        const int c0 = chunk * CH;
+        const int n = (A.Nq - c0) < CH ? (A.Nq - c0) : CH;   // multiple of 32
+        for (int i = tid; i < n; i += kThreads)
+#pragma unroll
+            for (int r = 0; r < NR; ++r) lg[r][i] = A.logits[((size_t)row * NR + r) * A.logit_stride + c0 + i];
+        __syncthreads();
+        if (A.slot_idx) {
+            for (int j = tid; j < L.topk; j += kThreads) {
+                const int t = A.slot_idx[(size_t)row * L.topk + j] - c0;
+                if (t >= 0 && t < n)
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) lg[r][t] = -INFINITY;
+            }
+            __syncthreads();
+        }
+        chunk_softmax<NR, CHX>(lg, n, red, m_row, l_row);
+
+        // p * s per (token, value group) and the zero-point term
+        float zacc[NR][M];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m) zacc[r][m] = 0.0f;
+        const uint32_t* vm_row = L.vm + (size_t)row * L.vm_stride;
+        for (int i = tid; i < n; i += kThreads) {
+            uint32_t meta[M];
+            if constexpr (M == 4) {
+                const uint4 t4 = *reinterpret_cast<const uint4*>(vm_row + (size_t)(c0 + i) * 4);
+                meta[0] = t4.x; meta[1] = t4.y; meta[2] = t4.z; meta[3] = t4.w;
+            } else {
+                const uint2 t2 = *reinterpret_cast<const uint2*>(vm_row + (size_t)(c0 + i) * 2);
+                meta[0] = t2.x; meta[1] = t2.y;
+            }
+            float p[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) p[r] = lg[r][i];
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                float s, z;
+                derive_scale_zero<BITS>(widen16<BF16>(meta[m] & 0xFFFFu), widen16<BF16>(meta[m] >> 16), s, z);
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    ps[((size_t)m * CH + i) * NR + r] = p[r] * s;
+                    zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                const float v = wave_sum(zacc[r][m]);
+                if (lane == 0) red[(wave * NR + r) * M + m] = v;
+            }
+        __syncthreads();
+
+        // sum_i (p_i s_i) code[i][c] for this lane's CPB channels
+        float acc[CPB][NR];
+#pragma unroll
+        for (int j = 0; j < CPB; ++j)
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[j][r] = 0.0f;
+        const uint8_t* vc_row = L.vc + (size_t)row * L.vc_stride + (size_t)(c0 / kBlockTokens) * code_block_bytes(BITS);
+        const int units = (n / kBlockTokens) * LPB;
+        const int within = lane % LPB;                       // position inside a block
+        const int Lc = within % (16 * BITS);                 // code lane: channels Lc*CPB .. +CPB-1
+        const int mgrp = (Lc * CPB) / GROUP;
+        for (int u = tid; u < units; u += kThreads) {
+            const int blk = u / LPB;
+            const uint4 w4 = *reinterpret_cast<const uint4*>(vc_row + (size_t)blk * code_block_bytes(BITS) + within * 16);
+            const int tbase = blk * kBlockTokens + (within / (16 * BITS)) * 16;
+            const float* psb = ps + ((size_t)mgrp * CH + tbase) * NR;
+#pragma unroll
+            for (int dq = 0; dq < 4; ++dq) {
+                const uint32_t w = comp(w4, dq);
+                float pv[4][NR];
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) pv[b][r] = psb[(dq * 4 + b) * NR + r];
+#pragma unroll
+                for (int j = 0; j < CPB; ++j) {
+                    const uint32_t mk = w & (MASK << (BITS * j));
+                    const float f0 = cvt_ubyte<0>(mk), f1 = cvt_ubyte<1>(mk), f2 = cvt_ubyte<2>(mk), f3 = cvt_ubyte<3>(mk);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        acc[j][r] = __builtin_fmaf(f0, pv[0][r], acc[j][r]);
+                        acc[j][r] = __builtin_fmaf(f1, pv[1][r], acc[j][r]);
+                        acc[j][r] = __builtin_fmaf(f2, pv[2][r], acc[j][r]);
+                        acc[j][r] = __builtin_fmaf(f3, pv[3][r], acc[j][r]);
+                    }
+                }
+            }
+        }
+        // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
+#pragma unroll
+        for (int j = 0; j < CPB; ++j)
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                float v = acc[j][r] * __uint_as_float((uint32_t)(127 - BITS * j) << 23);
+#pragma unroll
+                for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
+                acc[j][r] = v;
+            }
+        float zsum[NR][M];   // read before the region is reused
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int m = 0; m < M; ++m) {
+                float v = 0.0f;
+                for (int w = 0; w < kWaves; ++w) v += red[(w * NR + r) * M + m];
+                zsum[r][m] = v;
+            }
+        __syncthreads();   // everyone is done with lg / ps
+        if (lane < 16 * BITS) {
+#pragma unroll
+            for (int j = 0; j < CPB; ++j)
+#pragma unroll
+                for (int r = 0; r < NR; ++r) o_lds[((size_t)wave * NR + r) * kD + Lc * CPB + j] = acc[j][r];
+        }
+        __syncthreads();
+        for (int e = tid; e < NR * kD; e += kThreads) {
+            const int r = e / kD, c = e % kD;
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v += o_lds[((size_t)w * NR + r) * kD + c];
+            float zt = 0.0f;
+#pragma unroll
+            for (int rr = 0; rr < NR; ++rr)
+#pragma unroll
+                for (int m = 0; m < M; ++m)
+                    if (rr == r && m == c / GROUP) zt = zsum[rr][m];
+            po[e] = v + zt;
+        }
+    } else {
+        // ------------------------------------------------------------ 16-bit candidates
+        const int ks = A.slot_idx ? L.topk : 0;
+        const int n_res = A.N - A.Nq;
+        const int n_ex = ks + n_res + (A.k_spec ? 1 : 0);
+        const int x0 = (chunk - A.n_main) * kExtraChunk;
+        const int n = (n_ex - x0) < kExtraChunk ? (n_ex - x0) : kExtraChunk;
+        for (int e = tid; e < NR * kD; e += kThreads)
+            qf[e / kD][e % kD] = widen16<BF16>(A.q[((size_t)row * NR) * kD + e]) * A.sm_scale;
+        __syncthreads();
+
+        auto pair_ptr = [&](int x, const uint16_t*& kp, const uint16_t*& vp, bool& spec) -> bool {
+            spec = false;
+            if (x < ks) {
+                const int t = A.slot_idx[(size_t)row * L.topk + x];
+                if (t < 0 || t >= A.Nq) return false;
+                kp = A.slot + ((size_t)row * L.topk + x) * 256;
+                vp = kp + kD;
+                return true;
+            }
+            if (x < ks + n_res) {
+                const int t = A.Nq + (x - ks);
+                kp = L.ring + ((size_t)row * L.R + (t % L.R)) * 256;
+                vp = kp + kD;
+                return true;
+            }
+            spec = true;
+            kp = A.k_spec + (size_t)row * kD;
+            vp = A.v_spec + (size_t)row * kD;
+            return true;
+        };
+
+        // logits: 16 lanes per candidate, 8 channels per lane
+        const int sub = tid % 16;
+        for (int xl = tid / 16; xl < n; xl += kThreads / 16) {
+            const uint16_t *kp = nullptr, *vp = nullptr;
+            bool spec;
+            const bool valid = pair_ptr(x0 + xl, kp, vp, spec);
+            float part[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) part[r] = 0.0f;
+            if (valid) {
+                const uint4 kb = *reinterpret_cast<const uint4*>(kp + sub * 8);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const uint32_t w = comp(kb, d);
+                    const float k0 = widen16<BF16>(w & 0xFFFFu), k1 = widen16<BF16>(w >> 16);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        part[r] = __builtin_fmaf(qf[r][sub * 8 + 2 * d], k0, part[r]);
+                        part[r] = __builtin_fmaf(qf[r][sub * 8 + 2 * d + 1], k1, part[r]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                float v = part[r];
+#pragma unroll
+                for (int mask = 8; mask >= 1; mask >>= 1) v += __shfl_xor(v, mask, 64);
+                const bool sees = valid && (!spec || (r % NROWS == NROWS - 1));
+                if (sub == 0) lg[r][xl] = sees ? v : -INFINITY;
+            }
+        }
+        __syncthreads();
+        chunk_softmax<NR, CHX>(lg, n, red, m_row, l_row);
+
+        // sum_x p_x V[x][c]: thread = (channel, half of the candidates)
+        const int c = tid % kD, half = tid / kD;
+        float acc[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) acc[r] = 0.0f;
+        for (int xl = half; xl < n; xl += 2) {
+            bool any = false;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) any = any || lg[r][xl] != 0.0f;
+            if (!any) continue;   // also skips invalid slots, whose memory is never read
+            const uint16_t *kp = nullptr, *vp = nullptr;
+            bool spec;
+            pair_ptr(x0 + xl, kp, vp, spec);
+            const float v = widen16<BF16>(vp[c]);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[r] = __builtin_fmaf(lg[r][xl], v, acc[r]);
+        }
+        __syncthreads();   // done reading lg before the region is reused
+#pragma unroll
+        for (int r = 0; r < NR; ++r) o_lds[((size_t)half * NR + r) * kD + c] = acc[r];
+        __syncthreads();
+        for (int e = tid; e < NR * kD; e += kThreads) {
+            const int r = e / kD, cc = e % kD;
+            po[e] = o_lds[(size_t)r * kD + cc] + o_lds[((size_t)NR + r) * kD + cc];
+        }
+    }
+    if (tid < NR) {
+        float mv = 0.f, lv = 0.f;
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+            if (r == tid) { mv = m_row[r]; lv = l_row[r]; }
+        pml[2 * tid] = mv;
+        pml[2 * tid + 1] = lv;
+    }
+}
+
+// Merge the chunk partials of one (KV head, query row): o = sum_c o_c e^(m_c - m) / sum_c l_c e^(m_c - m).
+__global__ __launch_bounds__(kD) void attend_combine_kernel(const float* __restrict__ part_o,
+                                                            const float* __restrict__ part_ml, int max_chunks,
+                                                            int n_chunks, int NR, float* __restrict__ out) {
+    const int c = threadIdx.x;
+    const int row = blockIdx.x / NR, r = blockIdx.x % NR;
+    float mmax = -INFINITY;
+    for (int ch = 0; ch < n_chunks; ++ch)
+        mmax = fmaxf(mmax, part_ml[(((size_t)row * max_chunks + ch) * NR + r) * 2]);
+    float den = 0.0f, o = 0.0f;
+    for (int ch = 0; ch < n_chunks; ++ch) {
+        const size_t b = ((size_t)row * max_chunks + ch) * NR + r;
+        const float m = part_ml[b * 2];
+        if (m == -INFINITY) continue;
+        const float w = __expf(m - mmax);
+        den = __builtin_fmaf(part_ml[b * 2 + 1], w, den);
+        o = __builtin_fmaf(part_o[b * kD + c], w, o);
+    }
+    out[((size_t)row * NR + r) * kD + c] = o / den;
+}
+
+template <int BITS, int GROUP, int G, int NROWS>
+hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* out, hipStream_t stream) {
+    constexpr int NR = G * NROWS;
+    const dim3 grid(A.n_main + n_extra, L.rows), block(kThreads);
+    if (L.bf16)
+        hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, true>), grid, block, 0, stream, L, A);
+    else
+        hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, 0, stream, L, A);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(kD), 0, stream, A.part_o, A.part_ml,
+                       A.max_chunks, A.n_main + n_extra, NR, out);
+    return hipGetLastError();
+}
+
+template <int BITS, int GROUP>
+hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, float* out, hipStream_t stream) {
+#define SPC_CASE(g_, n_)                                                        \
+    if (L.G == g_ && n_rows == n_) {                                            \
+        A.n_main = (A.Nq + main_chunk(g_ * n_) - 1) / main_chunk(g_ * n_);      \
+        const int n_extra = (n_ex + kExtraChunk - 1) / kExtraChunk;             \
+        if (A.n_main + n_extra > A.max_chunks) return hipErrorInvalidValue;     \
+        return launch3<BITS, GROUP, g_, n_>(L, A, n_extra, out, stream);        \
+    }
+    SPC_CASE(1, 1) SPC_CASE(1, 2) SPC_CASE(2, 1) SPC_CASE(2, 2) SPC_CASE(4, 1) SPC_CASE(4, 2) SPC_CASE(8, 1)
+    SPC_CASE(8, 2)
+#undef SPC_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+int attend_main_chunk_tokens(int NR) { return main_chunk(NR); }
+int attend_extra_chunk_tokens() { return kExtraChunk; }
+
+hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
+                         const float* logits, size_t logit_stride, const uint16_t* slot, const int32_t* slot_idx,
+                         const void* k_spec, const void* v_spec, const AttendScratch& scratch, float* out,
+                         hipStream_t stream) {
+    AttendArgs A;
+    A.q = (const uint16_t*)q;
+    A.logits = logits;
+    A.logit_stride = logit_stride;
+    A.slot = slot;
+    A.slot_idx = slot_idx;
+    A.k_spec = (const uint16_t*)k_spec;
+    A.v_spec = (const uint16_t*)v_spec;
+    A.part_o = scratch.part_o;
+    A.part_ml = scratch.part_ml;
+    A.max_chunks = scratch.max_chunks;
+    A.n_main = 0;
+    A.N = N;
+    A.Nq = Nq;
+    A.sm_scale = sm_scale;
+    const int n_ex = (slot_idx ? L.topk : 0) + (N - Nq) + (k_spec ? 1 : 0);
+    if (L.bits == 2 && L.group == 32) return launch2<2, 32>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 2 && L.group == 64) return launch2<2, 64>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 1 && L.group == 32) return launch2<1, 32>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 1 && L.group == 64) return launch2<1, 64>(L, A, n_rows, n_ex, out, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace specache

@@ -1,0 +1,62 @@
+// Internal launch interface between the C-ABI host code (specache.hip) and the
+// kernel translation units.  Every launcher only enqueues on `stream` and
+// returns the hipGetLastError() of its launches.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specache {
+
+// Geometry and device pointers of one layer, as the kernels see them.
+struct LayerView {
+    int rows;          // B * Hkv
+    int G;             // query heads per KV head
+    int bits, group, R, max_seq, topk;
+    bool bf16;
+    uint8_t* kc;       // K codes   [rows][kc_stride bytes]
+    uint32_t* km;      // K meta    [rows][km_stride dwords]  ([group j][128])
+    uint8_t* vc;       // V codes   [rows][vc_stride bytes]
+    uint32_t* vm;      // V meta    [rows][vm_stride dwords]  ([token][128/g])
+    uint16_t* ring;    // residual  [rows][R][256] 16-bit
+    uint16_t* host;    // pinned C  [rows][max_seq][256] 16-bit (device-visible address)
+    size_t kc_stride, km_stride, vc_stride, vm_stride;
+};
+
+// quantize_append: flush `n_flush` groups starting at token Nq0, whose sources are
+// the ring (tokens < N0) or k_new/v_new (tokens >= N0, index t - N0 of n_new).
+hipError_t launch_flush(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0,
+                        int Nq0, int n_flush, hipStream_t stream);
+// copy the n_new tokens to the host store (all) and to the ring (tokens >= ring_from)
+hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0,
+                              int ring_from, hipStream_t stream);
+
+// score: logits [rows*G*n_rows][logit_stride] fp32 and keys [rows][key_stride] u32 for i < Nq
+hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
+                        size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
+
+// top-k over keys[row][0..Nq): idx_out [rows][k], ascending, -1 padded
+hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
+                       hipStream_t stream);
+
+// gather rows idx[row][j] of the host store into slot [rows][k][256] and slot_idx [rows][k]
+hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
+                         hipStream_t stream);
+
+// attend: partial pass + combine.  slot/slot_idx may be null (nothing prefetched).
+struct AttendScratch {
+    float* part_o;   // [rows][max_chunks][NR][128]
+    float* part_ml;  // [rows][max_chunks][NR][2]  (max, sum)
+    int max_chunks;
+};
+int attend_main_chunk_tokens(int NR);
+int attend_extra_chunk_tokens();
+hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
+                         const float* logits, size_t logit_stride, const uint16_t* slot,
+                         const int32_t* slot_idx, const void* k_spec, const void* v_spec,
+                         const AttendScratch& scratch, float* out, hipStream_t stream);
+
+// export: canonical unpacked view of rows' quantised prefix into device buffers
+hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz,
+                         uint8_t* v_codes, uint16_t* v_mnmx, float* v_sz, hipStream_t stream);
+
+}  // namespace specache

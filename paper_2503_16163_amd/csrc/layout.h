@@ -1,0 +1,112 @@
+// Device data layout of the low-bit cache C' and helpers shared by the kernels.
+//
+// All sizes are per (batch, KV head) "row" of a layer; head_dim D = 128.
+//
+// K codes (keys are grouped per channel over g tokens; Section 2.1 / 4.1):
+//   blocks of 32 tokens, each block = BITS planes of [32 tokens][16 bytes].
+//   A token's 128 codes occupy 4*BITS dwords; dword W (W = 4*plane + d) holds
+//   the 32/BITS channels c with c / (32/BITS) == W.  Inside a dword the code of
+//   channel c sits at bit 8*(w % 4) + BITS*(w / 4), w = c % (32/BITS): masking
+//   with (2^BITS - 1) * 0x01010101 << BITS*h leaves four codes, one per byte,
+//   each scaled by 2^(BITS*h); v_cvt_f32_ubyte{0..3} turns them into floats and
+//   the power of two is folded into the multiplier.  Byte b of that mask is
+//   channel 4*h + b of the dword, i.e. channel % 4 == b.
+//   A wave reads a plane of a block as 32 lanes x 16 B = 512 contiguous bytes.
+// K metadata: [token group j][channel c] one dword = min | max << 16 (16-bit
+//   patterns of the cache dtype); scale and zero-point are derived on use.
+// V codes (values are grouped per token over g channels):
+//   blocks of 32 tokens, each block = [2 halves of 16 tokens][16*BITS lanes][16 B];
+//   byte t of a lane's 16 bytes is token 16*half + t and holds the 8/BITS
+//   channels c with c / (8/BITS) == lane, channel c at bit BITS * (c % (8/BITS)).
+//   The same mask-and-convert form then yields four tokens of one channel.
+// V metadata: [token][channel group m] one dword = min | max << 16.
+// Residual ring, staging slots and the pinned host store share one row format:
+//   512 bytes per token = K row (128 x 16 bit) then V row.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace specache {
+
+constexpr int kD = 128;          // head_dim
+constexpr int kRowBytes = 512;   // one 16-bit (K,V) pair
+constexpr int kBlockTokens = 32; // tokens per code block
+
+__host__ __device__ constexpr int code_block_bytes(int bits) { return 512 * bits; }
+
+// ---- 16-bit -> float, exact --------------------------------------------------
+template <bool BF16>
+__device__ __forceinline__ float widen16(uint32_t bits16) {
+    if constexpr (BF16) {
+        return __uint_as_float(bits16 << 16);
+    } else {
+        _Float16 h;
+        uint16_t u = (uint16_t)bits16;
+        __builtin_memcpy(&h, &u, 2);
+        return (float)h;
+    }
+}
+
+// ---- Eq. 2 / Eq. 3: scale and zero-point from the stored (min, max) -----------
+// Every step is a single IEEE binary32 operation (no contraction): the integer
+// codes depend on it.
+template <int BITS>
+__device__ __forceinline__ void derive_scale_zero(float mn, float mx, float& s, float& z) {
+    const float range = __fsub_rn(mx, mn);
+    if constexpr (BITS == 1) {
+        z = __fmul_rn(__fadd_rn(__fmul_rn(3.0f, mn), mx), 0.25f);
+        s = __fmul_rn(range, 0.5f);
+    } else {
+        constexpr float cB = (float)(1.0 / (double)((1 << BITS) - 1));
+        z = mn;
+        s = __fmul_rn(range, cB);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t quantize_one(float x, float s, float z) {
+    if (s == 0.0f) return 0u;
+    const float t = __fdiv_rn(__fsub_rn(x, z), s);
+    const float r = floorf(__fadd_rn(t, 0.5f));
+    int c = (int)r;
+    c = c < 0 ? 0 : c;
+    c = c > ((1 << BITS) - 1) ? ((1 << BITS) - 1) : c;
+    return (uint32_t)c;
+}
+
+// ---- K code addressing ---------------------------------------------------------
+template <int BITS>
+__host__ __device__ __forceinline__ int k_dword_of_channel(int c) { return c / (32 / BITS); }
+template <int BITS>
+__host__ __device__ __forceinline__ int k_bit_of_channel(int c) {
+    const int w = c % (32 / BITS);
+    return 8 * (w % 4) + BITS * (w / 4);
+}
+// byte offset, inside a row's K code area, of dword W of token t
+template <int BITS>
+__host__ __device__ __forceinline__ size_t k_dword_offset(int t, int W) {
+    const int blk = t / kBlockTokens, tok = t % kBlockTokens, plane = W / 4, d = W % 4;
+    return (size_t)blk * code_block_bytes(BITS) + (size_t)plane * 512 + (size_t)tok * 16 + (size_t)d * 4;
+}
+
+// ---- V code addressing ---------------------------------------------------------
+template <int BITS>
+__host__ __device__ __forceinline__ int v_lane_of_channel(int c) { return c / (8 / BITS); }
+template <int BITS>
+__host__ __device__ __forceinline__ int v_bit_of_channel(int c) {
+    return BITS * (c % (8 / BITS));
+}
+// byte offset, inside a row's V code area, of the byte of (token t, lane L)
+template <int BITS>
+__host__ __device__ __forceinline__ size_t v_byte_offset(int t, int L) {
+    const int blk = t / kBlockTokens, tok = t % kBlockTokens, half = tok / 16, tt = tok % 16;
+    return (size_t)blk * code_block_bytes(BITS) + ((size_t)half * (16 * BITS) + L) * 16 + tt;
+}
+
+// order-preserving map float -> uint32 (larger float <=> larger key); -0 joins +0
+__device__ __forceinline__ uint32_t float_to_key(float f) {
+    const uint32_t u = __float_as_uint(f + 0.0f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace specache

@@ -1,0 +1,354 @@
+// C ABI of the SpeCache decode-step library (see include/specache.h): argument
+// checks, buffer ownership, the append bookkeeping of the residual policy and the
+// stream/event protocol between the main stream and the prefetch side stream.
+// All arithmetic of the method lives in the kernels.
+#include "../../include/specache.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "layout.h"
+
+using namespace specache;
+
+namespace {
+
+struct Layer {
+    LayerView view{};
+    int N = 0, Nq = 0;
+    void* host_alloc = nullptr;
+    uint16_t* slot[2] = {nullptr, nullptr};
+    int32_t* slot_idx[2] = {nullptr, nullptr};
+    bool slot_filled[2] = {false, false};
+    hipEvent_t gathered[2] = {nullptr, nullptr};
+    hipEvent_t attended[2] = {nullptr, nullptr};
+    bool attended_recorded[2] = {false, false};
+    hipEvent_t idx_ready = nullptr;
+    bool idx_ready_recorded = false;
+    const int32_t* last_gather_idx = nullptr;
+    int last_gather_slot = -1;
+};
+
+thread_local std::string g_create_error;
+
+}  // namespace
+
+struct specache_ctx {
+    specache_config cfg{};
+    int device = 0;
+    float sm_scale = 0.f;
+    std::vector<Layer> layers;
+    float* logits = nullptr;     // [rows*G*2][logit_stride]
+    uint32_t* keys = nullptr;    // [rows][logit_stride]
+    size_t logit_stride = 0;
+    AttendScratch scratch{};
+    int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
+    std::string err;
+};
+
+namespace {
+
+int fail(specache_ctx* ctx, int code, const std::string& msg) {
+    if (ctx) ctx->err = msg; else g_create_error = msg;
+    return code;
+}
+
+int fail_hip(specache_ctx* ctx, hipError_t e, const char* what) {
+    (void)hipGetLastError();
+    return fail(ctx, e == hipErrorOutOfMemory ? SPECACHE_ENOMEM : SPECACHE_EHIP,
+                std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define SPC_HIP(ctx, call)                                     \
+    do {                                                       \
+        hipError_t e_ = (call);                                \
+        if (e_ != hipSuccess) return fail_hip(ctx, e_, #call); \
+    } while (0)
+
+int check_ctx_layer(specache_ctx* ctx, int32_t layer) {
+    if (!ctx) return SPECACHE_EINVAL;
+    if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, SPECACHE_EINVAL, "layer out of range");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, SPECACHE_EINVAL, "the context's device is not the current HIP device");
+    return SPECACHE_OK;
+}
+
+void free_all(specache_ctx* ctx) {
+    for (Layer& L : ctx->layers) {
+        (void)hipFree(L.view.kc);
+        (void)hipFree(L.view.km);
+        (void)hipFree(L.view.vc);
+        (void)hipFree(L.view.vm);
+        (void)hipFree(L.view.ring);
+        if (L.host_alloc) (void)hipHostFree(L.host_alloc);
+        for (int s = 0; s < 2; ++s) {
+            (void)hipFree(L.slot[s]);
+            (void)hipFree(L.slot_idx[s]);
+            if (L.gathered[s]) (void)hipEventDestroy(L.gathered[s]);
+            if (L.attended[s]) (void)hipEventDestroy(L.attended[s]);
+        }
+        if (L.idx_ready) (void)hipEventDestroy(L.idx_ready);
+    }
+    (void)hipFree(ctx->logits);
+    (void)hipFree(ctx->keys);
+    (void)hipFree(ctx->scratch.part_o);
+    (void)hipFree(ctx->scratch.part_ml);
+}
+
+}  // namespace
+
+extern "C" {
+
+int specache_plan_append(int32_t residual, int32_t group, int32_t n_tokens, int32_t n_quantized, int32_t n_new,
+                         int32_t* n_flush_groups) {
+    if (group <= 0 || residual < group || residual % group || n_tokens < n_quantized || n_quantized < 0 ||
+        n_tokens - n_quantized >= residual || n_new < 0 || !n_flush_groups)
+        return SPECACHE_EINVAL;
+    const long total = (long)(n_tokens - n_quantized) + n_new;
+    *n_flush_groups = total >= residual ? (int32_t)((total - residual) / group + 1) : 0;
+    return SPECACHE_OK;
+}
+
+int specache_create(const specache_config* cfg, specache_ctx** out) {
+    if (out) *out = nullptr;
+    if (!cfg || !out) return fail(nullptr, SPECACHE_EINVAL, "null config or output pointer");
+    const specache_config& c = *cfg;
+    if (c.n_layers < 1 || c.batch < 1 || c.n_kv_heads < 1 || c.n_q_heads < 1)
+        return fail(nullptr, SPECACHE_EINVAL, "n_layers, batch and head counts must be positive");
+    if (c.n_q_heads % c.n_kv_heads) return fail(nullptr, SPECACHE_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    const int G = c.n_q_heads / c.n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8) return fail(nullptr, SPECACHE_EINVAL, "n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
+    if (c.head_dim != kD) return fail(nullptr, SPECACHE_EINVAL, "head_dim must be 128");
+    if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
+    if (c.group != 32 && c.group != 64) return fail(nullptr, SPECACHE_EINVAL, "group must be 32 or 64");
+    if (c.residual < c.group || c.residual % c.group || c.residual > 256)
+        return fail(nullptr, SPECACHE_EINVAL, "residual must be a multiple of group in [group, 256]");
+    if (c.max_seq < 64 || c.max_seq % 64) return fail(nullptr, SPECACHE_EINVAL, "max_seq must be a positive multiple of 64");
+    if (c.topk < 1 || c.topk > 4096) return fail(nullptr, SPECACHE_EINVAL, "topk must be in [1, 4096]");
+    if (c.dtype != SPECACHE_FP16 && c.dtype != SPECACHE_BF16) return fail(nullptr, SPECACHE_EINVAL, "dtype must be fp16 or bf16");
+
+    specache_ctx* ctx = new (std::nothrow) specache_ctx();
+    if (!ctx) return fail(nullptr, SPECACHE_ENOMEM, "host allocation failed");
+    ctx->cfg = c;
+    ctx->sm_scale = c.sm_scale > 0.f ? c.sm_scale : 1.0f / std::sqrt((float)kD);
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) { delete ctx; return fail_hip(nullptr, e, "hipGetDevice"); }
+
+    const int rows = c.batch * c.n_kv_heads;
+    const size_t cap = (size_t)c.max_seq;
+    ctx->layers.resize(c.n_layers);
+    auto bail = [&](hipError_t err, const char* what) {
+        const int rc = fail_hip(nullptr, err, what);
+        free_all(ctx);
+        delete ctx;
+        return rc;
+    };
+#define SPC_ALLOC(call)                               \
+    do {                                              \
+        hipError_t e_ = (call);                       \
+        if (e_ != hipSuccess) return bail(e_, #call); \
+    } while (0)
+
+    for (Layer& L : ctx->layers) {
+        LayerView& v = L.view;
+        v.rows = rows; v.G = G; v.bits = c.bits; v.group = c.group; v.R = c.residual;
+        v.max_seq = c.max_seq; v.topk = c.topk; v.bf16 = c.dtype == SPECACHE_BF16;
+        v.kc_stride = cap / kBlockTokens * code_block_bytes(c.bits);
+        v.vc_stride = v.kc_stride;
+        v.km_stride = cap / c.group * kD;
+        v.vm_stride = cap * (kD / c.group);
+        SPC_ALLOC(hipMalloc((void**)&v.kc, rows * v.kc_stride));
+        SPC_ALLOC(hipMalloc((void**)&v.vc, rows * v.vc_stride));
+        SPC_ALLOC(hipMalloc((void**)&v.km, rows * v.km_stride * 4));
+        SPC_ALLOC(hipMalloc((void**)&v.vm, rows * v.vm_stride * 4));
+        SPC_ALLOC(hipMalloc((void**)&v.ring, (size_t)rows * c.residual * kRowBytes));
+        SPC_ALLOC(hipHostMalloc(&L.host_alloc, (size_t)rows * cap * kRowBytes, hipHostMallocDefault));
+        void* dev_view = nullptr;
+        SPC_ALLOC(hipHostGetDevicePointer(&dev_view, L.host_alloc, 0));
+        v.host = (uint16_t*)dev_view;
+        for (int s = 0; s < 2; ++s) {
+            SPC_ALLOC(hipMalloc((void**)&L.slot[s], (size_t)rows * c.topk * kRowBytes));
+            SPC_ALLOC(hipMalloc((void**)&L.slot_idx[s], (size_t)rows * c.topk * 4));
+            SPC_ALLOC(hipMemset(L.slot_idx[s], 0xFF, (size_t)rows * c.topk * 4));
+            SPC_ALLOC(hipEventCreateWithFlags(&L.gathered[s], hipEventDisableTiming));
+            SPC_ALLOC(hipEventCreateWithFlags(&L.attended[s], hipEventDisableTiming));
+        }
+        SPC_ALLOC(hipEventCreateWithFlags(&L.idx_ready, hipEventDisableTiming));
+    }
+    ctx->logit_stride = cap;
+    SPC_ALLOC(hipMalloc((void**)&ctx->logits, (size_t)rows * G * 2 * cap * 4));
+    SPC_ALLOC(hipMalloc((void**)&ctx->keys, (size_t)rows * cap * 4));
+    int max_main = 0;
+    for (int n = 1; n <= 2; ++n) {
+        const int ch = attend_main_chunk_tokens(G * n);
+        const int m = (int)((cap + ch - 1) / ch);
+        max_main = m > max_main ? m : max_main;
+    }
+    const int ec = attend_extra_chunk_tokens();
+    ctx->scratch.max_chunks = max_main + (c.topk + c.residual + 1 + ec - 1) / ec;
+    SPC_ALLOC(hipMalloc((void**)&ctx->scratch.part_o, (size_t)rows * ctx->scratch.max_chunks * G * 2 * kD * 4));
+    SPC_ALLOC(hipMalloc((void**)&ctx->scratch.part_ml, (size_t)rows * ctx->scratch.max_chunks * G * 2 * 2 * 4));
+    SPC_ALLOC(hipDeviceSynchronize());
+#undef SPC_ALLOC
+    *out = ctx;
+    return SPECACHE_OK;
+}
+
+int specache_destroy(specache_ctx* ctx) {
+    if (!ctx) return SPECACHE_OK;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+    return SPECACHE_OK;
+}
+
+const char* specache_last_error(const specache_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int specache_counts(const specache_ctx* ctx, int32_t layer, int32_t* n_tokens, int32_t* n_quantized) {
+    if (!ctx || layer < 0 || layer >= ctx->cfg.n_layers) return SPECACHE_EINVAL;
+    if (n_tokens) *n_tokens = ctx->layers[layer].N;
+    if (n_quantized) *n_quantized = ctx->layers[layer].Nq;
+    return SPECACHE_OK;
+}
+
+int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, int32_t n_new,
+                             void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (n_new < 0 || (n_new > 0 && (!k_new || !v_new))) return fail(ctx, SPECACHE_EINVAL, "null k_new/v_new or negative n_new");
+    if (n_new == 0) return SPECACHE_OK;
+    Layer& L = ctx->layers[layer];
+    if ((long)L.N + n_new > ctx->cfg.max_seq) return fail(ctx, SPECACHE_ECAPACITY, "append exceeds max_seq");
+    int32_t n_flush = 0;
+    if (specache_plan_append(ctx->cfg.residual, ctx->cfg.group, L.N, L.Nq, n_new, &n_flush) != SPECACHE_OK)
+        return fail(ctx, SPECACHE_ESTATE, "inconsistent token counts");
+    const int Nq1 = L.Nq + n_flush * ctx->cfg.group, N1 = L.N + n_new;
+    hipStream_t st = (hipStream_t)stream;
+    // the flush reads residual tokens from the ring, so it precedes the ring update
+    SPC_HIP(ctx, launch_flush(L.view, k_new, v_new, n_new, L.N, L.Nq, n_flush, st));
+    SPC_HIP(ctx, launch_append_copy(L.view, k_new, v_new, n_new, L.N, Nq1 > L.N ? Nq1 : L.N, st));
+    L.N = N1;
+    L.Nq = Nq1;
+    return SPECACHE_OK;
+}
+
+int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, int32_t* topk_idx_out,
+                        void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!q || !topk_idx_out) return fail(ctx, SPECACHE_EINVAL, "null q or topk_idx_out");
+    if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    Layer& L = ctx->layers[layer];
+    hipStream_t st = (hipStream_t)stream;
+    // a gather still reading this index buffer must finish before it is overwritten
+    if (L.last_gather_idx == topk_idx_out && L.last_gather_slot >= 0)
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
+    SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
+                              ctx->logit_stride, st));
+    SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out, st));
+    SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
+    L.idx_ready_recorded = true;
+    ctx->scored_layer = layer;
+    ctx->scored_rows = n_rows;
+    ctx->scored_N = L.N;
+    ctx->scored_Nq = L.Nq;
+    return SPECACHE_OK;
+}
+
+int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_t slot, void* side_stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!idx) return fail(ctx, SPECACHE_EINVAL, "null idx");
+    if (slot != 0 && slot != 1) return fail(ctx, SPECACHE_EINVAL, "slot must be 0 or 1");
+    Layer& L = ctx->layers[layer];
+    hipStream_t st = (hipStream_t)side_stream;
+    if (L.idx_ready_recorded) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
+    if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
+    SPC_HIP(ctx, launch_gather(L.view, idx, L.slot[slot], L.slot_idx[slot], st));
+    SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
+    L.slot_filled[slot] = true;
+    L.last_gather_idx = idx;
+    L.last_gather_slot = slot;
+    return SPECACHE_OK;
+}
+
+int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                    const void* v_spec, int32_t slot, float* out, void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!q || !out) return fail(ctx, SPECACHE_EINVAL, "null q or out");
+    if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    if ((k_spec == nullptr) != (v_spec == nullptr)) return fail(ctx, SPECACHE_EINVAL, "k_spec and v_spec must both be given or both be null");
+    if (slot < -1 || slot > 1) return fail(ctx, SPECACHE_EINVAL, "slot must be -1, 0 or 1");
+    Layer& L = ctx->layers[layer];
+    if (ctx->scored_layer != layer || ctx->scored_rows != n_rows || ctx->scored_N != L.N || ctx->scored_Nq != L.Nq)
+        return fail(ctx, SPECACHE_ESTATE, "attend must follow score_topk of the same layer, n_rows and cache state");
+    if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
+    if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
+    hipStream_t st = (hipStream_t)stream;
+    if (slot >= 0) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
+    SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
+                               slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
+                               v_spec, ctx->scratch, out, st));
+    if (slot >= 0) {
+        SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
+        L.attended_recorded[slot] = true;
+    }
+    return SPECACHE_OK;
+}
+
+int specache_export_quantized(specache_ctx* ctx, int32_t layer, uint8_t* k_codes, uint16_t* k_minmax,
+                              float* k_scale_zero, uint8_t* v_codes, uint16_t* v_minmax, float* v_scale_zero) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    Layer& L = ctx->layers[layer];
+    SPC_HIP(ctx, hipDeviceSynchronize());
+    const size_t rows = L.view.rows, Nq = L.Nq, g = ctx->cfg.group;
+    if (Nq == 0) return SPECACHE_OK;
+    const size_t n_codes = rows * Nq * kD, n_kg = rows * (Nq / g) * kD, n_vg = rows * Nq * (kD / g);
+    struct Buf { void* host; size_t bytes; void* dev; };
+    Buf bufs[6] = {{k_codes, n_codes, nullptr},        {k_minmax, n_kg * 4, nullptr}, {k_scale_zero, n_kg * 8, nullptr},
+                   {v_codes, n_codes, nullptr},        {v_minmax, n_vg * 4, nullptr}, {v_scale_zero, n_vg * 8, nullptr}};
+    int rc = SPECACHE_OK;
+    for (Buf& b : bufs)
+        if (b.host && rc == SPECACHE_OK) {
+            hipError_t e = hipMalloc(&b.dev, b.bytes);
+            if (e != hipSuccess) rc = fail_hip(ctx, e, "hipMalloc(export)");
+        }
+    if (rc == SPECACHE_OK) {
+        hipError_t e = launch_export(L.view, L.Nq, (uint8_t*)bufs[0].dev, (uint16_t*)bufs[1].dev, (float*)bufs[2].dev,
+                                     (uint8_t*)bufs[3].dev, (uint16_t*)bufs[4].dev, (float*)bufs[5].dev, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        for (Buf& b : bufs)
+            if (b.dev && e == hipSuccess) e = hipMemcpy(b.host, b.dev, b.bytes, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) rc = fail_hip(ctx, e, "export");
+    }
+    for (Buf& b : bufs) (void)hipFree(b.dev);
+    return rc;
+}
+
+int specache_export_rows(specache_ctx* ctx, int32_t layer, int32_t first, int32_t count, uint16_t* out) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    Layer& L = ctx->layers[layer];
+    if (!out || first < 0 || count < 0 || first + count > L.N) return fail(ctx, SPECACHE_EINVAL, "bad row range or null output");
+    SPC_HIP(ctx, hipDeviceSynchronize());
+    const uint8_t* src = (const uint8_t*)L.host_alloc;
+    for (int r = 0; r < L.view.rows; ++r)
+        std::memcpy((uint8_t*)out + (size_t)r * count * kRowBytes,
+                    src + ((size_t)r * ctx->cfg.max_seq + first) * kRowBytes, (size_t)count * kRowBytes);
+    return SPECACHE_OK;
+}
+
+int specache_debug_logits(specache_ctx* ctx, float* out) {
+    if (!ctx || !out) return SPECACHE_EINVAL;
+    if (ctx->scored_layer < 0) return fail(ctx, SPECACHE_ESTATE, "nothing scored yet");
+    SPC_HIP(ctx, hipDeviceSynchronize());
+    const size_t n = (size_t)ctx->layers[ctx->scored_layer].view.rows * ctx->layers[ctx->scored_layer].view.G * ctx->scored_rows;
+    const size_t Nq = ctx->scored_Nq;
+    if (Nq == 0) return SPECACHE_OK;
+    SPC_HIP(ctx, hipMemcpy2D(out, Nq * 4, ctx->logits, ctx->logit_stride * 4, Nq * 4, n, hipMemcpyDeviceToHost));
+    return SPECACHE_OK;
+}
+
+}  // extern "C"

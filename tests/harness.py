@@ -1,0 +1,170 @@
+"""Shared driver for the GPU-vs-oracle parity tests and the smoke check.
+
+Runs the HIP path through the C ABI (paper_2503_16163_amd.binding) and the CPU
+oracle on the same seeded synthetic inputs and compares them to the bars:
+  * codes, stored (min,max) and derived (s,z): bit-exact;
+  * offloaded 16-bit rows: bit-exact;
+  * top-k index sets: equal, except positions whose oracle score lies within
+    1e-5 * max(|tau|, max|sigma|) of the k-th score tau;
+  * attention outputs: max |o - o_ref| / max(max|o_ref|, 1e-6) <= 2e-3 per
+    (head, row).
+"""
+import numpy as np
+import torch
+
+from oracle import oracle as orc
+from paper_2503_16163_amd import binding, synth
+
+OUT_TOL = 2e-3
+TIE_BAND = 1e-5
+# fp32 accumulation of 128 products against the oracle's double: a few 1e-6 of the
+# largest partial sum; checked loosely, the gates are the two bars above.
+LOGIT_TOL = 2e-4
+
+
+def to_dev(bits, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    return t.view(torch.float16 if dtype == synth.FP16 else torch.bfloat16)
+
+
+def check_topk(sigma, idx, k, what=""):
+    """Band rule for one row.  sigma: oracle scores [Nq] (float64); idx: GPU result [k]."""
+    nq = sigma.size
+    keff = min(k, nq)
+    sel = idx[:keff]
+    assert np.all(idx[keff:] == -1), f"{what}: padding"
+    assert np.all(sel >= 0) and np.all(sel < nq), f"{what}: index range"
+    assert np.all(np.diff(sel) > 0), f"{what}: not strictly ascending"
+    if keff == 0:
+        return 0
+    order = np.sort(sigma)[::-1]
+    tau = order[keff - 1]
+    band = TIE_BAND * max(abs(tau), np.abs(sigma).max())
+    chosen = np.zeros(nq, bool)
+    chosen[sel] = True
+    must = sigma > tau + band
+    must_not = sigma < tau - band
+    assert np.all(chosen[must]), f"{what}: a position above the tie band is missing"
+    assert not np.any(chosen[must_not]), f"{what}: a position below the tie band was selected"
+    ref = orc.topk(sigma, k)[:keff]
+    return int(keff - np.intersect1d(ref, sel).size)   # differences inside the band
+
+
+def check_out(out_gpu, out_ref, what=""):
+    """out_*: [G, rows, D]."""
+    denom = np.maximum(np.abs(out_ref).max(axis=-1), 1e-6)
+    err = np.abs(out_gpu.astype(np.float64) - out_ref).max(axis=-1) / denom
+    assert np.all(np.isfinite(out_gpu)), f"{what}: non-finite output"
+    assert err.max() <= OUT_TOL, f"{what}: attention output error {err.max():.3e} > {OUT_TOL}"
+    return float(err.max())
+
+
+class Case:
+    """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
+
+    def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
+                 max_seq=None, n_outlier=4):
+        self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
+        self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
+        self.sm_scale = 1.0 / np.sqrt(128.0)
+        self.sample = sample if sample is not None else [(b, h) for b in range(B) for h in range(Hkv)]
+        cap = max_seq or ((S + 64 + 63) // 64) * 64
+        self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R)
+        self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
+        self.oc = {}
+        self.side = torch.cuda.Stream()
+        self.idx = [torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)]
+        self.step_no = 0
+        self.stats = dict(band_diffs=0, max_out_err=0.0, max_logit_err=0.0)
+
+    def close(self):
+        torch.cuda.synchronize()
+        self.sc.close()
+
+    # ---- load ---------------------------------------------------------------
+    def load(self, chunks=None):
+        """Bulk append of the S prompt tokens (optionally split into several calls)."""
+        S = self.S
+        bounds = [0, S] if not chunks else [0] + list(chunks) + [S]
+        for a, b in zip(bounds[:-1], bounds[1:]):
+            if b > a:
+                kd = to_dev(self.k_bits[:, :, a:b], self.dtype)
+                vd = to_dev(self.v_bits[:, :, a:b], self.dtype)
+                self.sc.quantize_append(0, kd, vd, b - a)
+        torch.cuda.synchronize()
+        for (b, h) in self.sample:
+            c = orc.Cache(self.D, self.bits, self.g, self.R, self.dtype)
+            c.append(self.k_bits[b, h], self.v_bits[b, h])
+            self.oc[(b, h)] = c
+
+    def append_token(self, t):
+        kb, vb = synth.make_step_kv(self.seed, t, self.B, self.Hkv, self.D, self.dtype)
+        self.sc.quantize_append(0, to_dev(kb, self.dtype), to_dev(vb, self.dtype), 1)
+        for (b, h) in self.sample:
+            self.oc[(b, h)].append(kb[b, h], vb[b, h])
+        self.k_bits = np.concatenate([self.k_bits, kb], axis=2)
+        self.v_bits = np.concatenate([self.v_bits, vb], axis=2)
+
+    # ---- checks -------------------------------------------------------------
+    def check_quantized(self):
+        e = self.sc.export_quantized(0)
+        n, nq = self.sc.counts(0)
+        for (b, h) in self.sample:
+            c = self.oc[(b, h)]
+            assert c.counts() == (n, nq), ("counts", c.counts(), (n, nq))
+            o = c.export()
+            assert np.array_equal(e["k_codes"][b, h], o["k_codes"]), f"K codes differ at {(b, h)}"
+            assert np.array_equal(e["v_codes"][b, h], o["v_codes"]), f"V codes differ at {(b, h)}"
+            assert np.array_equal(e["k_mnmx"][b, h], synth.to_bits(o["k_mnmx"], self.dtype)), "K (min,max)"
+            assert np.array_equal(e["v_mnmx"][b, h], synth.to_bits(o["v_mnmx"], self.dtype)), "V (min,max)"
+            assert np.array_equal(e["k_sz"][b, h].view(np.uint32), o["k_sz"].view(np.uint32)), "K (s,z)"
+            assert np.array_equal(e["v_sz"][b, h].view(np.uint32), o["v_sz"].view(np.uint32)), "V (s,z)"
+        return n, nq
+
+    def check_offload(self, first=0, count=None):
+        n, _ = self.sc.counts(0)
+        count = n - first if count is None else count
+        rows = self.sc.export_rows(0, first, count)
+        assert np.array_equal(rows[:, :, :, 0], self.k_bits[:, :, first:first + count])
+        assert np.array_equal(rows[:, :, :, 1], self.v_bits[:, :, first:first + count])
+
+    def decode_step(self, use_spec=True, check_logits=True, do_gather=True):
+        """score_topk -> gather(next slot) -> attend(current slot), each checked against the oracle."""
+        t = self.step_no
+        nr = self.n_rows
+        q_bits = synth.make_queries(self.seed, self.B, self.Hq, self.D, self.dtype, n_rows=nr, sub=t)
+        ks_bits, vs_bits = synth.make_spec_kv(self.seed, self.B, self.Hkv, self.D, self.dtype, sub=t)
+        q = to_dev(q_bits, self.dtype)
+        ks, vs = (to_dev(ks_bits, self.dtype), to_dev(vs_bits, self.dtype)) if use_spec else (None, None)
+        idx = self.idx[t % 2]
+        main = torch.cuda.current_stream()
+        self.sc.score_topk(0, q, nr, idx, main)
+        if do_gather:
+            self.sc.gather(0, idx, (t + 1) % 2, self.side)
+        out = torch.empty((self.B, self.Hq, nr, self.D), dtype=torch.float32, device="cuda")
+        slot = (t % 2) if (t > 0 and do_gather) else -1
+        self.sc.attend(0, q, nr, ks, vs, slot, out, main)
+        torch.cuda.synchronize()
+        idx_h = idx.cpu().numpy()
+        out_h = out.cpu().numpy()
+        logits_h = self.sc.debug_logits(0, nr) if check_logits else None
+        prev = self.prev_idx if slot >= 0 else None
+        n, nq = self.sc.counts(0)
+        for (b, h) in self.sample:
+            c = self.oc[(b, h)]
+            qh = q_bits[b, h * self.G:(h + 1) * self.G]                      # [G, rows, D]
+            ref_logits, sigma = c.scores(qh, self.sm_scale)
+            if check_logits and nq:
+                got = logits_h[b, h * self.G:(h + 1) * self.G]
+                err = np.abs(got - ref_logits).max() / max(np.abs(ref_logits).max(), 1.0)
+                self.stats["max_logit_err"] = max(self.stats["max_logit_err"], float(err))
+                assert err <= LOGIT_TOL, f"logits differ at {(b, h)}: {err:.3e}"
+            self.stats["band_diffs"] += check_topk(sigma, idx_h[b, h], self.k, what=f"top-k {(b, h)} step {t}")
+            P = prev[b, h] if prev is not None else None
+            ref_out = c.attend(qh, self.sm_scale, P=P, k_spec=ks_bits[b, h, 0] if use_spec else None,
+                               v_spec=vs_bits[b, h, 0] if use_spec else None)
+            e = check_out(out_h[b, h * self.G:(h + 1) * self.G], ref_out, what=f"attend {(b, h)} step {t}")
+            self.stats["max_out_err"] = max(self.stats["max_out_err"], e)
+        self.prev_idx = idx_h
+        self.step_no += 1
+        return idx_h, out_h

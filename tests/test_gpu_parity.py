@@ -1,0 +1,156 @@
+"""GPU-vs-oracle parity through the C ABI (run with -m gpu on an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_16163_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    binding.lib()
+
+
+def _run(case, steps=3, chunks=None, use_spec=True):
+    from tests import harness  # noqa: F401
+    try:
+        case.load(chunks=chunks)
+        n, nq = case.check_quantized()
+        case.check_offload()
+        for t in range(steps):
+            case.append_token(t)
+            case.decode_step(use_spec=use_spec)
+        case.check_quantized()
+        case.check_offload(first=case.S, count=steps)
+        return case.stats
+    finally:
+        case.close()
+
+
+def test_config1_single_head():
+    """BASELINE config 1: B=1, 1 head, S=4096, fp16, 2-bit g32, k=64."""
+    from tests.harness import Case
+    stats = _run(Case(1, 1, 1, 4096, synth.FP16, 2, 32, 64, seed=1001), steps=4)
+    print("config1", stats)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,dtype,bits,g,k,R", [
+    (2, 3, 3, 1500, synth.FP16, 2, 32, 128, 64),     # MHA, ragged tail (1500 = 46*32 + 28)
+    (1, 8, 2, 2112, synth.BF16, 2, 64, 96, 64),      # GQA 4:1, g = R = 64 (ring empties on flush)
+    (1, 8, 2, 1200, synth.BF16, 1, 32, 200, 64),     # 1-bit GQA
+    (2, 2, 2, 777, synth.FP16, 1, 64, 33, 128),      # 1-bit g64, R = 128, odd k
+    (1, 4, 2, 900, synth.FP16, 2, 32, 64, 96),       # GQA 2:1, R = 96
+    (1, 8, 1, 640, synth.BF16, 2, 32, 40, 64),       # GQA 8:1
+])
+def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
+    from tests.harness import Case
+    stats = _run(Case(B, Hq, Hkv, S, dtype, bits, g, k, R=R, seed=2000 + S), steps=3)
+    print(stats)
+
+
+def test_streamed_load_equals_bulk_load():
+    """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
+    from tests.harness import Case
+    c = Case(1, 2, 2, 333, synth.FP16, 2, 32, 16, seed=2100)
+    _run(c, steps=2, chunks=[1, 2, 50, 63, 64, 65, 200, 201, 202, 203, 204, 300])
+
+
+def test_pre_decoding_single_row():
+    """n_rows = 1 (Appendix A "Pre-decoding"): selection on the only row, nothing prefetched."""
+    from tests.harness import Case
+    c = Case(1, 4, 2, 700, synth.FP16, 2, 32, 50, seed=2200, n_rows=1)
+    try:
+        c.load()
+        c.decode_step(use_spec=False, do_gather=False)
+    finally:
+        c.close()
+
+
+def test_short_cache_edges():
+    """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
+    from tests.harness import Case
+    c = Case(1, 2, 1, 40, synth.BF16, 2, 32, 64, seed=2300)
+    try:
+        c.load()
+        assert c.sc.counts(0) == (40, 0)
+        idx, _ = c.decode_step()
+        assert np.all(idx == -1)
+        for t in range(30):          # crosses the first flush at N = 64
+            c.append_token(t)
+        assert c.sc.counts(0) == (70, 32)
+        c.check_quantized()
+        idx, _ = c.decode_step()
+        assert np.array_equal(idx[0, 0, :32], np.arange(32)) and np.all(idx[0, 0, 32:] == -1)
+        c.decode_step()              # uses the slot gathered with k_eff = 32 < k
+    finally:
+        c.close()
+    c = Case(1, 1, 1, 1, synth.FP16, 1, 32, 8, seed=2301)
+    try:
+        c.load()
+        c.decode_step()
+    finally:
+        c.close()
+
+
+def test_all_positions_prefetched_matches_full_attention():
+    """k >= Nq: every low-bit pair is replaced, so the GPU output equals textbook attention."""
+    from tests.harness import Case
+    from oracle import oracle as orc
+    c = Case(1, 2, 2, 300, synth.FP16, 2, 32, 512, seed=2400)
+    try:
+        c.load()
+        c.decode_step()
+        _, out = c.decode_step()
+        t = 1
+        q_bits = synth.make_queries(c.seed, 1, 2, 128, c.dtype, sub=t)
+        ks, vs = synth.make_spec_kv(c.seed, 1, 2, 128, c.dtype, sub=t)
+        for h in range(2):
+            ref = c.oc[(0, h)].full_attention(q_bits[0, h:h + 1], c.sm_scale, k_spec=ks[0, h, 0], v_spec=vs[0, h, 0])
+            from tests.harness import check_out
+            check_out(out[0, h:h + 1], ref, what="full attention")
+    finally:
+        c.close()
+
+
+def test_error_paths():
+    sc = binding.SpeCache(2, 1, 2, 2, 2, 32, 256, 16, synth.FP16)
+    try:
+        k = torch.zeros((1, 2, 300, 128), dtype=torch.float16, device="cuda")
+        q = torch.zeros((1, 2, 2, 128), dtype=torch.float16, device="cuda")
+        idx = torch.zeros((1, 2, 16), dtype=torch.int32, device="cuda")
+        out = torch.zeros((1, 2, 2, 128), dtype=torch.float32, device="cuda")
+        for fn, code in [
+            (lambda: sc.quantize_append(0, k, k, 300), binding.ECAPACITY),
+            (lambda: sc.quantize_append(5, k, k, 1), binding.EINVAL),
+            (lambda: sc.quantize_append(0, None, k, 1), binding.EINVAL),
+            (lambda: sc.score_topk(0, q, 3, idx), binding.EINVAL),
+            (lambda: sc.gather(0, idx, 2), binding.EINVAL),
+            (lambda: sc.attend(0, q, 2, None, None, -1, out), binding.ESTATE),   # nothing scored
+        ]:
+            with pytest.raises(binding.SpeCacheError) as ei:
+                fn()
+            assert ei.value.code == code
+        sc.quantize_append(0, k, k, 100)
+        sc.score_topk(0, q, 2, idx)
+        with pytest.raises(binding.SpeCacheError) as ei:
+            sc.attend(0, q, 2, None, None, 0, out)                               # slot never gathered
+        assert ei.value.code == binding.ESTATE
+        with pytest.raises(binding.SpeCacheError) as ei:
+            sc.attend(1, q, 2, None, None, -1, out)                              # other layer
+        assert ei.value.code == binding.ESTATE
+        sc.attend(0, q, 2, None, None, -1, out)
+        torch.cuda.synchronize()
+        assert sc.counts(0) == (100, 64) and sc.counts(1) == (0, 0)
+    finally:
+        sc.close()
+    for kwargs in [dict(bits=3), dict(group=48), dict(residual=48), dict(max_seq=100), dict(topk=0), dict(head_dim=64),
+                   dict(n_q_heads=3, n_kv_heads=2)]:
+        base = dict(n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, bits=2, group=32, max_seq=256, topk=16,
+                    dtype=synth.FP16)
+        base.update(kwargs)
+        with pytest.raises(binding.SpeCacheError) as ei:
+            binding.SpeCache(**base)
+        assert ei.value.code == binding.EINVAL
