@@ -174,6 +174,26 @@ int specache_export_quantized(specache_ctx* ctx, int32_t layer, uint8_t* k_codes
 int specache_export_rows(specache_ctx* ctx, int32_t layer, int32_t first, int32_t count, uint16_t* out);
 int specache_debug_logits(specache_ctx* ctx, float* out);
 
+/*
+ * Measurement hook.  While enabled, every hot call brackets each of its kernel
+ * phases with a pair of HIP events on the stream the phase is launched on.
+ * specache_timing synchronises the device, adds up the elapsed time of all
+ * pairs recorded since the previous call into total_us[SPECACHE_K_COUNT] (host,
+ * microseconds) and launches[SPECACHE_K_COUNT] (host), forgets them, and then
+ * switches recording on (enable != 0) or off.  Either output may be NULL.
+ * SPECACHE_K_ATTEND covers the partial and the combine kernel together.
+ */
+enum {
+    SPECACHE_K_FLUSH = 0,       /* quantise + pack of full groups            */
+    SPECACHE_K_APPEND_COPY = 1, /* offload to host store + residual update   */
+    SPECACHE_K_SCORE = 2,       /* fused dequantise + q.K^T                  */
+    SPECACHE_K_TOPK = 3,        /* radix select + ordered compaction         */
+    SPECACHE_K_GATHER = 4,      /* host-link gather (side stream)            */
+    SPECACHE_K_ATTEND = 5,      /* mixed attention: partial + combine        */
+    SPECACHE_K_COUNT = 6
+};
+int specache_timing(specache_ctx* ctx, int32_t enable, double* total_us, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

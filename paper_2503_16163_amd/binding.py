@@ -17,7 +17,8 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
-           "specache_attend", "specache_export_quantized", "specache_export_rows", "specache_debug_logits"]
+           "specache_attend", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
+           "specache_timing"]
 
 
 class Config(C.Structure):
@@ -55,6 +56,7 @@ def lib():
         L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
         L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
         L.specache_debug_logits.argtypes = [vp, vp]
+        L.specache_timing.argtypes = [vp, i32, vp, vp]
         for name in EXPORTS:
             if name != "specache_last_error":
                 getattr(L, name).restype = C.c_int
@@ -130,6 +132,15 @@ class SpeCache:
     def attend(self, layer, q, n_rows, k_spec, v_spec, slot, out, stream=None):
         self._check(lib().specache_attend(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
                                           _ptr(out), _stream(stream)))
+
+    KERNELS = ("flush", "append_copy", "score", "topk", "gather", "attend")
+
+    def timing(self, enable):
+        """Collect and reset per-kernel event timings; returns {kernel: (total_us, launches)}."""
+        us = (C.c_double * len(self.KERNELS))()
+        n = (C.c_int64 * len(self.KERNELS))()
+        self._check(lib().specache_timing(self._ctx, int(bool(enable)), us, n))
+        return {k: (us[i], n[i]) for i, k in enumerate(self.KERNELS)}
 
     # ---- parity hooks (host numpy arrays) ------------------------------------
     def export_quantized(self, layer):

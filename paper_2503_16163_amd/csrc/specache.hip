@@ -49,6 +49,11 @@ struct specache_ctx {
     AttendScratch scratch{};
     int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
     std::string err;
+    // optional per-kernel timing: (start, stop) event pairs recorded around each launch
+    bool timing = false;
+    std::vector<hipEvent_t> ev_pool;
+    struct Span { int kind; hipEvent_t a, b; };
+    std::vector<Span> spans;
 };
 
 namespace {
@@ -69,6 +74,30 @@ int fail_hip(specache_ctx* ctx, hipError_t e, const char* what) {
         hipError_t e_ = (call);                                \
         if (e_ != hipSuccess) return fail_hip(ctx, e_, #call); \
     } while (0)
+
+// Brackets one launcher call with a pair of timing events when timing is on.
+struct TimedLaunch {
+    specache_ctx* ctx;
+    hipStream_t st;
+    int kind;
+    hipEvent_t a = nullptr, b = nullptr;
+    static hipEvent_t take(specache_ctx* c) {
+        if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        return hipEventCreate(&e) == hipSuccess ? e : nullptr;
+    }
+    TimedLaunch(specache_ctx* c, hipStream_t s, int k) : ctx(c), st(s), kind(k) {
+        if (!c->timing) return;
+        a = take(c);
+        b = take(c);
+        if (a) (void)hipEventRecord(a, st);
+    }
+    ~TimedLaunch() {
+        if (!a || !b) return;
+        (void)hipEventRecord(b, st);
+        ctx->spans.push_back({kind, a, b});
+    }
+};
 
 int check_ctx_layer(specache_ctx* ctx, int32_t layer) {
     if (!ctx) return SPECACHE_EINVAL;
@@ -95,6 +124,8 @@ void free_all(specache_ctx* ctx) {
         }
         if (L.idx_ready) (void)hipEventDestroy(L.idx_ready);
     }
+    for (auto& sp : ctx->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+    for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     (void)hipFree(ctx->logits);
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->scratch.part_o);
@@ -230,8 +261,14 @@ int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new
     const int Nq1 = L.Nq + n_flush * ctx->cfg.group, N1 = L.N + n_new;
     hipStream_t st = (hipStream_t)stream;
     // the flush reads residual tokens from the ring, so it precedes the ring update
-    SPC_HIP(ctx, launch_flush(L.view, k_new, v_new, n_new, L.N, L.Nq, n_flush, st));
-    SPC_HIP(ctx, launch_append_copy(L.view, k_new, v_new, n_new, L.N, Nq1 > L.N ? Nq1 : L.N, st));
+    if (n_flush > 0) {
+        TimedLaunch t(ctx, st, SPECACHE_K_FLUSH);
+        SPC_HIP(ctx, launch_flush(L.view, k_new, v_new, n_new, L.N, L.Nq, n_flush, st));
+    }
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_APPEND_COPY);
+        SPC_HIP(ctx, launch_append_copy(L.view, k_new, v_new, n_new, L.N, Nq1 > L.N ? Nq1 : L.N, st));
+    }
     L.N = N1;
     L.Nq = Nq1;
     return SPECACHE_OK;
@@ -247,9 +284,15 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     // a gather still reading this index buffer must finish before it is overwritten
     if (L.last_gather_idx == topk_idx_out && L.last_gather_slot >= 0)
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
-    SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
-                              ctx->logit_stride, st));
-    SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out, st));
+    if (L.Nq > 0) {
+        TimedLaunch t(ctx, st, SPECACHE_K_SCORE);
+        SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
+                                  ctx->logit_stride, st));
+    }
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_TOPK);
+        SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out, st));
+    }
     SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;
     ctx->scored_layer = layer;
@@ -267,7 +310,10 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     hipStream_t st = (hipStream_t)side_stream;
     if (L.idx_ready_recorded) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
     if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
-    SPC_HIP(ctx, launch_gather(L.view, idx, L.slot[slot], L.slot_idx[slot], st));
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
+        SPC_HIP(ctx, launch_gather(L.view, idx, L.slot[slot], L.slot_idx[slot], st));
+    }
     SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
     L.slot_filled[slot] = true;
     L.last_gather_idx = idx;
@@ -289,9 +335,12 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
     hipStream_t st = (hipStream_t)stream;
     if (slot >= 0) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
-    SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
-                               slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
-                               v_spec, ctx->scratch, out, st));
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_ATTEND);
+        SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
+                                   slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
+                                   v_spec, ctx->scratch, out, st));
+    }
     if (slot >= 0) {
         SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
         L.attended_recorded[slot] = true;
@@ -337,6 +386,25 @@ int specache_export_rows(specache_ctx* ctx, int32_t layer, int32_t first, int32_
     for (int r = 0; r < L.view.rows; ++r)
         std::memcpy((uint8_t*)out + (size_t)r * count * kRowBytes,
                     src + ((size_t)r * ctx->cfg.max_seq + first) * kRowBytes, (size_t)count * kRowBytes);
+    return SPECACHE_OK;
+}
+
+int specache_timing(specache_ctx* ctx, int32_t enable, double* total_us, int64_t* launches) {
+    if (!ctx) return SPECACHE_EINVAL;
+    SPC_HIP(ctx, hipDeviceSynchronize());
+    if (total_us) for (int k = 0; k < SPECACHE_K_COUNT; ++k) total_us[k] = 0.0;
+    if (launches) for (int k = 0; k < SPECACHE_K_COUNT; ++k) launches[k] = 0;
+    for (auto& sp : ctx->spans) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) {
+            if (total_us) total_us[sp.kind] += 1e3 * (double)ms;
+            if (launches) launches[sp.kind] += 1;
+        }
+        ctx->ev_pool.push_back(sp.a);
+        ctx->ev_pool.push_back(sp.b);
+    }
+    ctx->spans.clear();
+    ctx->timing = enable != 0;
     return SPECACHE_OK;
 }
 

@@ -89,3 +89,44 @@ def make_step_kv(seed, step, B, Hkv, D, dtype, n_outlier=4, outlier_scale=10.0):
             for h in range(Hkv):
                 k[b, h][:, ch[b, h]] *= np.float32(outlier_scale)
     return to_bits(k, dtype), to_bits(v, dtype)
+
+
+# ---- the same recipe drawn on the GPU (full-size benchmark inputs) ------------
+
+def torch_dtype(dtype):
+    import torch
+    return torch.float16 if dtype == FP16 else torch.bfloat16
+
+
+def make_kv_device(seed, B, Hkv, S, D, dtype, n_outlier=4, outlier_scale=10.0, device="cuda"):
+    """K, V as 16-bit tensors [B, Hkv, S, D] on the device, drawn with torch's seeded generator."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    k = torch.randn((B, Hkv, S, D), generator=gen, device=device, dtype=torch.float32)
+    if n_outlier:
+        ch = outlier_channels(seed, B, Hkv, D, n_outlier)
+        scale = torch.ones((B, Hkv, 1, D), device=device)
+        for b in range(B):
+            for h in range(Hkv):
+                scale[b, h, 0, torch.as_tensor(ch[b, h], device=device)] = outlier_scale
+        k *= scale
+    k = k.to(torch_dtype(dtype))
+    v = torch.randn((B, Hkv, S, D), generator=gen, device=device, dtype=torch.float32).to(torch_dtype(dtype))
+    return k, v
+
+
+def make_queries_device(seed, n, B, Hq, D, dtype, device="cuda"):
+    """n query tensors [n, B, Hq, 2, D]: row 0 = q ~ N(0,1), row 1 = q + 0.1 N(0,1)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed + 7919)
+    q = torch.randn((n, B, Hq, 1, D), generator=gen, device=device, dtype=torch.float32)
+    dq = torch.randn((n, B, Hq, 1, D), generator=gen, device=device, dtype=torch.float32)
+    return torch.cat([q, q + 0.1 * dq], dim=3).to(torch_dtype(dtype)).contiguous()
+
+
+def bits_of(t):
+    """uint16 numpy view of a 16-bit torch tensor (copied to the host)."""
+    import torch
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
