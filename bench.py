@@ -47,6 +47,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
+    ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -74,7 +75,8 @@ def main():
             if e.code != binding.ENOMEM or layers == 1:
                 raise
             layers = max(1, layers // 2)   # the pinned host store did not fit: fewer layers
-    main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
+    main_s = torch.cuda.current_stream()
+    side_s = main_s if args.serial_gather else torch.cuda.Stream()
 
     # ---- load the prompt: the same synthetic K/V tensor serves every layer ----------
     kd, vd = synth.make_kv_device(seed, B, Hkv, S, D, dtype)

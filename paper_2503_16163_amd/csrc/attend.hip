@@ -124,15 +124,27 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     constexpr int LPB = 32 * BITS;           // lanes per 32-token block
     constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
     constexpr int CHX = CH > kExtraChunk ? CH : kExtraChunk;
-    // region A: lg[NR][CHX] then ps[M][CH][NR]; reused as o_lds[kWaves][NR][128] at the end
-    constexpr int kLg = NR * CHX, kPs = M * CH * NR, kOl = kWaves * NR * kD;
-    constexpr int kRegion = (kLg + kPs) > kOl ? (kLg + kPs) : kOl;
+    constexpr int TPT = (CH + kThreads - 1) / kThreads;   // chunk tokens per thread
+    // one region: ps[M][CH][NR] (main chunks) or lg[NR][CHX] (extra chunks); reused as
+    // o_lds[kWaves][NR][128] at the end
+    // ps is stored in cells [16-token half block][value group m] of 16*NR floats plus one
+    // 16-byte pad: the lanes of one LDS read differ only in (half block, m), i.e. in
+    // consecutive cells, and the pad spreads those over distinct banks.
+    constexpr int kCell = 16 * NR + 4;
+    constexpr int kLg = NR * CHX, kPs = (CH / 16) * M * kCell, kOl = kWaves * NR * kD;
+    constexpr int kRegion = kLg > kPs ? (kLg > kOl ? kLg : kOl) : (kPs > kOl ? kPs : kOl);
     __shared__ __attribute__((aligned(16))) float smem[kRegion];
     __shared__ float red[kWaves * NR * (1 + M)];
+    __shared__ float red_sum[kWaves * NR];
+    __shared__ float red_z[kWaves * NR * M];
+    __shared__ uint32_t maskbits[CH / 32];
     __shared__ float qf[NR][kD];
+    __shared__ const uint16_t* src_k[kExtraChunk];
+    __shared__ const uint16_t* src_v[kExtraChunk];
+    __shared__ bool src_spec[kExtraChunk];
 
     float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
-    float* ps = smem + kLg;                  // [M][CH][NR]
+    float* ps = smem;                        // [CH/16][M] cells
     float* o_lds = smem;                     // [kWaves][NR][128]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -145,59 +157,122 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
         // ------------------------------------------------------------ quantised positions
         const int c0 = chunk * CH;
         const int n = (A.Nq - c0) < CH ? (A.Nq - c0) : CH;   // multiple of 32
-        for (int i = tid; i < n; i += kThreads)
+        const uint8_t* vc_row = L.vc + (size_t)row * L.vc_stride + (size_t)(c0 / kBlockTokens) * code_block_bytes(BITS);
+        const uint32_t* vm_row = L.vm + (size_t)row * L.vm_stride;
+        const int units = (n / kBlockTokens) * LPB;
+        const int within = lane % LPB;                       // position inside a block
+        const int Lc = within % (16 * BITS);                 // code lane: channels Lc*CPB .. +CPB-1
+        const int mgrp = (Lc * CPB) / GROUP;
+        const uint8_t* vc_lane = vc_row + within * 16;
+
+        // every global read this thread needs before the value loop is issued up front
+        float lgr[TPT][NR];
+        uint32_t meta[TPT][M];
 #pragma unroll
-            for (int r = 0; r < NR; ++r) lg[r][i] = A.logits[((size_t)row * NR + r) * A.logit_stride + c0 + i];
+        for (int tt = 0; tt < TPT; ++tt) {
+            const int i = tid + tt * kThreads;
+            const bool valid = i < n;
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+                lgr[tt][r] = valid ? A.logits[((size_t)row * NR + r) * A.logit_stride + c0 + i] : -INFINITY;
+            if constexpr (M == 4) {
+                const uint4 t4 = valid ? *reinterpret_cast<const uint4*>(vm_row + (size_t)(c0 + i) * 4) : make_uint4(0, 0, 0, 0);
+                meta[tt][0] = t4.x; meta[tt][1] = t4.y; meta[tt][2] = t4.z; meta[tt][3] = t4.w;
+            } else {
+                const uint2 t2 = valid ? *reinterpret_cast<const uint2*>(vm_row + (size_t)(c0 + i) * 2) : make_uint2(0, 0);
+                meta[tt][0] = t2.x; meta[tt][1] = t2.y;
+            }
+        }
+        uint4 w4 = make_uint4(0, 0, 0, 0);
+        if (tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
+
+        // prefetched positions of this chunk, as a bitmap
+        if (tid < CH / 32) maskbits[tid] = 0u;
         __syncthreads();
         if (A.slot_idx) {
             for (int j = tid; j < L.topk; j += kThreads) {
                 const int t = A.slot_idx[(size_t)row * L.topk + j] - c0;
-                if (t >= 0 && t < n)
-#pragma unroll
-                    for (int r = 0; r < NR; ++r) lg[r][t] = -INFINITY;
+                if (t >= 0 && t < n) atomicOr(&maskbits[t >> 5], 1u << (t & 31));
             }
-            __syncthreads();
         }
-        chunk_softmax<NR, CHX>(lg, n, red, m_row, l_row);
+        __syncthreads();
 
-        // p * s per (token, value group) and the zero-point term
-        float zacc[NR][M];
+        float mloc[NR];
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+        for (int r = 0; r < NR; ++r) mloc[r] = -INFINITY;
+#pragma unroll
+        for (int tt = 0; tt < TPT; ++tt) {
+            const int i = tid + tt * kThreads;
+            const bool masked = i < n && ((maskbits[i >> 5] >> (i & 31)) & 1u);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                if (masked) lgr[tt][r] = -INFINITY;
+                mloc[r] = fmaxf(mloc[r], lgr[tt][r]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const float v = wave_max(mloc[r]);
+            if (lane == 0) red[wave * NR + r] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            float v = red[r];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) v = fmaxf(v, red[w * NR + r]);
+            m_row[r] = v;
+        }
+
+        // p = exp(l - m); p * s per (token, value group); the zero-point term; the row sums
+        float zacc[NR][M], sloc[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            sloc[r] = 0.0f;
 #pragma unroll
             for (int m = 0; m < M; ++m) zacc[r][m] = 0.0f;
-        const uint32_t* vm_row = L.vm + (size_t)row * L.vm_stride;
-        for (int i = tid; i < n; i += kThreads) {
-            uint32_t meta[M];
-            if constexpr (M == 4) {
-                const uint4 t4 = *reinterpret_cast<const uint4*>(vm_row + (size_t)(c0 + i) * 4);
-                meta[0] = t4.x; meta[1] = t4.y; meta[2] = t4.z; meta[3] = t4.w;
-            } else {
-                const uint2 t2 = *reinterpret_cast<const uint2*>(vm_row + (size_t)(c0 + i) * 2);
-                meta[0] = t2.x; meta[1] = t2.y;
-            }
-            float p[NR];
+        }
 #pragma unroll
-            for (int r = 0; r < NR; ++r) p[r] = lg[r][i];
-#pragma unroll
-            for (int m = 0; m < M; ++m) {
-                float s, z;
-                derive_scale_zero<BITS>(widen16<BF16>(meta[m] & 0xFFFFu), widen16<BF16>(meta[m] >> 16), s, z);
+        for (int tt = 0; tt < TPT; ++tt) {
+            const int i = tid + tt * kThreads;
+            if (i < n) {
+                float p[NR];
 #pragma unroll
                 for (int r = 0; r < NR; ++r) {
-                    ps[((size_t)m * CH + i) * NR + r] = p[r] * s;
-                    zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                    const float ms = m_row[r] == -INFINITY ? 0.0f : m_row[r];
+                    p[r] = __expf(lgr[tt][r] - ms);
+                    sloc[r] += p[r];
+                }
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    float sc, z;
+                    derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
+                        zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                    }
                 }
             }
         }
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+        for (int r = 0; r < NR; ++r) {
+            const float v = wave_sum(sloc[r]);
+            if (lane == 0) red_sum[wave * NR + r] = v;
 #pragma unroll
             for (int m = 0; m < M; ++m) {
-                const float v = wave_sum(zacc[r][m]);
-                if (lane == 0) red[(wave * NR + r) * M + m] = v;
+                const float zv = wave_sum(zacc[r][m]);
+                if (lane == 0) red_z[(wave * NR + r) * M + m] = zv;
             }
+        }
         __syncthreads();
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            float v = red_sum[r];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) v += red_sum[w * NR + r];
+            l_row[r] = v;
+        }
 
         // sum_i (p_i s_i) code[i][c] for this lane's CPB channels
         float acc[CPB][NR];
@@ -205,16 +280,13 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
         for (int j = 0; j < CPB; ++j)
 #pragma unroll
             for (int r = 0; r < NR; ++r) acc[j][r] = 0.0f;
-        const uint8_t* vc_row = L.vc + (size_t)row * L.vc_stride + (size_t)(c0 / kBlockTokens) * code_block_bytes(BITS);
-        const int units = (n / kBlockTokens) * LPB;
-        const int within = lane % LPB;                       // position inside a block
-        const int Lc = within % (16 * BITS);                 // code lane: channels Lc*CPB .. +CPB-1
-        const int mgrp = (Lc * CPB) / GROUP;
         for (int u = tid; u < units; u += kThreads) {
             const int blk = u / LPB;
-            const uint4 w4 = *reinterpret_cast<const uint4*>(vc_row + (size_t)blk * code_block_bytes(BITS) + within * 16);
-            const int tbase = blk * kBlockTokens + (within / (16 * BITS)) * 16;
-            const float* psb = ps + ((size_t)mgrp * CH + tbase) * NR;
+            uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
+            if (u + kThreads < units)
+                w4n = *reinterpret_cast<const uint4*>(vc_lane + (size_t)((u + kThreads) / LPB) * code_block_bytes(BITS));
+            const int hb = blk * 2 + within / (16 * BITS);   // 16-token half block inside the chunk
+            const float* psb = ps + (hb * M + mgrp) * kCell;
 #pragma unroll
             for (int dq = 0; dq < 4; ++dq) {
                 const uint32_t w = comp(w4, dq);
@@ -236,6 +308,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                     }
                 }
             }
+            w4 = w4n;
         }
         // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
 #pragma unroll
@@ -253,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 #pragma unroll
             for (int m = 0; m < M; ++m) {
                 float v = 0.0f;
-                for (int w = 0; w < kWaves; ++w) v += red[(w * NR + r) * M + m];
+                for (int w = 0; w < kWaves; ++w) v += red_z[(w * NR + r) * M + m];
                 zsum[r][m] = v;
             }
         __syncthreads();   // everyone is done with lg / ps
@@ -288,47 +361,55 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             qf[e / kD][e % kD] = widen16<BF16>(A.q[((size_t)row * NR) * kD + e]) * A.sm_scale;
         __syncthreads();
 
-        auto pair_ptr = [&](int x, const uint16_t*& kp, const uint16_t*& vp, bool& spec) -> bool {
-            spec = false;
+        // where each candidate's (K,V) pair lives; null = not a candidate (unused staging entry)
+        if (tid < n) {
+            const int x = x0 + tid;
+            const uint16_t* kp = nullptr;
+            bool spec = false;
             if (x < ks) {
                 const int t = A.slot_idx[(size_t)row * L.topk + x];
-                if (t < 0 || t >= A.Nq) return false;
-                kp = A.slot + ((size_t)row * L.topk + x) * 256;
-                vp = kp + kD;
-                return true;
-            }
-            if (x < ks + n_res) {
+                if (t >= 0 && t < A.Nq) kp = A.slot + ((size_t)row * L.topk + x) * 256;
+            } else if (x < ks + n_res) {
                 const int t = A.Nq + (x - ks);
                 kp = L.ring + ((size_t)row * L.R + (t % L.R)) * 256;
-                vp = kp + kD;
-                return true;
+            } else {
+                spec = true;
             }
-            spec = true;
-            kp = A.k_spec + (size_t)row * kD;
-            vp = A.v_spec + (size_t)row * kD;
-            return true;
-        };
+            src_k[tid] = spec ? A.k_spec + (size_t)row * kD : kp;
+            src_v[tid] = spec ? A.v_spec + (size_t)row * kD : (kp ? kp + kD : nullptr);
+            src_spec[tid] = spec;
+        }
+        __syncthreads();
 
-        // logits: 16 lanes per candidate, 8 channels per lane
-        const int sub = tid % 16;
-        for (int xl = tid / 16; xl < n; xl += kThreads / 16) {
-            const uint16_t *kp = nullptr, *vp = nullptr;
-            bool spec;
-            const bool valid = pair_ptr(x0 + xl, kp, vp, spec);
+        // logits: 16 lanes per candidate, 8 channels per lane; all key loads of a thread issued first
+        constexpr int kPass = kExtraChunk / (kThreads / 16);
+        const int sub = tid % 16, grp = tid / 16;
+        uint4 kb[kPass];
+#pragma unroll
+        for (int p = 0; p < kPass; ++p) {
+            const int xl = grp + p * (kThreads / 16);
+            const uint16_t* kp = xl < n ? src_k[xl] : nullptr;
+            kb[p] = kp ? *reinterpret_cast<const uint4*>(kp + sub * 8) : make_uint4(0, 0, 0, 0);
+        }
+        float qreg[NR][8];
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int d = 0; d < 8; ++d) qreg[r][d] = qf[r][sub * 8 + d];
+#pragma unroll
+        for (int p = 0; p < kPass; ++p) {
+            const int xl = grp + p * (kThreads / 16);
             float part[NR];
 #pragma unroll
             for (int r = 0; r < NR; ++r) part[r] = 0.0f;
-            if (valid) {
-                const uint4 kb = *reinterpret_cast<const uint4*>(kp + sub * 8);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const uint32_t w = comp(kb, d);
-                    const float k0 = widen16<BF16>(w & 0xFFFFu), k1 = widen16<BF16>(w >> 16);
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t w = comp(kb[p], d);
+                const float k0 = widen16<BF16>(w & 0xFFFFu), k1 = widen16<BF16>(w >> 16);
 #pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        part[r] = __builtin_fmaf(qf[r][sub * 8 + 2 * d], k0, part[r]);
-                        part[r] = __builtin_fmaf(qf[r][sub * 8 + 2 * d + 1], k1, part[r]);
-                    }
+                for (int r = 0; r < NR; ++r) {
+                    part[r] = __builtin_fmaf(qreg[r][2 * d], k0, part[r]);
+                    part[r] = __builtin_fmaf(qreg[r][2 * d + 1], k1, part[r]);
                 }
             }
 #pragma unroll
@@ -336,37 +417,62 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 float v = part[r];
 #pragma unroll
                 for (int mask = 8; mask >= 1; mask >>= 1) v += __shfl_xor(v, mask, 64);
-                const bool sees = valid && (!spec || (r % NROWS == NROWS - 1));
-                if (sub == 0) lg[r][xl] = sees ? v : -INFINITY;
+                if (sub == 0 && xl < n) {
+                    const bool sees = src_k[xl] != nullptr && (!src_spec[xl] || (r % NROWS == NROWS - 1));
+                    lg[r][xl] = sees ? v : -INFINITY;
+                }
             }
         }
         __syncthreads();
         chunk_softmax<NR, CHX>(lg, n, red, m_row, l_row);
 
-        // sum_x p_x V[x][c]: thread = (channel, half of the candidates)
-        const int c = tid % kD, half = tid / kD;
-        float acc[NR];
+        // sum_x p_x V[x][c]: thread = (channel pair, quarter of the candidates), loads in batches of 8
+        const int cp = tid % 64, quarter = tid / 64;
+        float acc[NR][2];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) acc[r] = 0.0f;
-        for (int xl = half; xl < n; xl += 2) {
-            bool any = false;
+        for (int r = 0; r < NR; ++r) acc[r][0] = acc[r][1] = 0.0f;
+        constexpr int kPerQuarter = kExtraChunk / 4;
 #pragma unroll
-            for (int r = 0; r < NR; ++r) any = any || lg[r][xl] != 0.0f;
-            if (!any) continue;   // also skips invalid slots, whose memory is never read
-            const uint16_t *kp = nullptr, *vp = nullptr;
-            bool spec;
-            pair_ptr(x0 + xl, kp, vp, spec);
-            const float v = widen16<BF16>(vp[c]);
+        for (int b0 = 0; b0 < kPerQuarter; b0 += 8) {
+            uint32_t vw[8];
 #pragma unroll
-            for (int r = 0; r < NR; ++r) acc[r] = __builtin_fmaf(lg[r][xl], v, acc[r]);
+            for (int u = 0; u < 8; ++u) {
+                const int xl = quarter * kPerQuarter + b0 + u;
+                bool any = false;
+                if (xl < n) {
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) any = any || lg[r][xl] != 0.0f;
+                }
+                // weight 0 (also every unused staging entry): its memory is never read
+                vw[u] = any ? *reinterpret_cast<const uint32_t*>(src_v[xl] + 2 * cp) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int xl = quarter * kPerQuarter + b0 + u;
+                if (xl < n) {
+                    const float v0 = widen16<BF16>(vw[u] & 0xFFFFu), v1 = widen16<BF16>(vw[u] >> 16);
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        const float p = lg[r][xl];
+                        acc[r][0] = __builtin_fmaf(p, v0, acc[r][0]);
+                        acc[r][1] = __builtin_fmaf(p, v1, acc[r][1]);
+                    }
+                }
+            }
         }
         __syncthreads();   // done reading lg before the region is reused
 #pragma unroll
-        for (int r = 0; r < NR; ++r) o_lds[((size_t)half * NR + r) * kD + c] = acc[r];
+        for (int r = 0; r < NR; ++r) {
+            o_lds[((size_t)quarter * NR + r) * kD + 2 * cp] = acc[r][0];
+            o_lds[((size_t)quarter * NR + r) * kD + 2 * cp + 1] = acc[r][1];
+        }
         __syncthreads();
         for (int e = tid; e < NR * kD; e += kThreads) {
             const int r = e / kD, cc = e % kD;
-            po[e] = o_lds[(size_t)r * kD + cc] + o_lds[((size_t)NR + r) * kD + cc];
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v += o_lds[((size_t)w * NR + r) * kD + cc];
+            po[e] = v;
         }
     }
     if (tid < NR) {
@@ -380,24 +486,70 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 }
 
 // Merge the chunk partials of one (KV head, query row): o = sum_c o_c e^(m_c - m) / sum_c l_c e^(m_c - m).
-__global__ __launch_bounds__(kD) void attend_combine_kernel(const float* __restrict__ part_o,
-                                                            const float* __restrict__ part_ml, int max_chunks,
-                                                            int n_chunks, int NR, float* __restrict__ out) {
-    const int c = threadIdx.x;
+// 256 threads = 4 slices of the chunk list x 64 channel pairs; the chunk weights are
+// computed once into LDS so that the partial-output loads are independent of each other.
+constexpr int kCombineMaxChunks = 1280;
+__global__ __launch_bounds__(256) void attend_combine_kernel(const float* __restrict__ part_o,
+                                                             const float* __restrict__ part_ml, int max_chunks,
+                                                             int n_chunks, int NR, float* __restrict__ out) {
+    __shared__ float wgt[kCombineMaxChunks];
+    __shared__ float red[8];
+    __shared__ float2 osum[4][64];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int row = blockIdx.x / NR, r = blockIdx.x % NR;
-    float mmax = -INFINITY;
-    for (int ch = 0; ch < n_chunks; ++ch)
-        mmax = fmaxf(mmax, part_ml[(((size_t)row * max_chunks + ch) * NR + r) * 2]);
-    float den = 0.0f, o = 0.0f;
-    for (int ch = 0; ch < n_chunks; ++ch) {
-        const size_t b = ((size_t)row * max_chunks + ch) * NR + r;
-        const float m = part_ml[b * 2];
-        if (m == -INFINITY) continue;
-        const float w = __expf(m - mmax);
-        den = __builtin_fmaf(part_ml[b * 2 + 1], w, den);
-        o = __builtin_fmaf(part_o[b * kD + c], w, o);
+    const float* ml = part_ml + ((size_t)row * max_chunks * NR + r) * 2;
+    const size_t ml_stride = (size_t)NR * 2;
+    float mloc = -INFINITY;
+    for (int ch = tid; ch < n_chunks; ch += 256) {
+        const float m = ml[ch * ml_stride];
+        wgt[ch] = m;
+        mloc = fmaxf(mloc, m);
     }
-    out[((size_t)row * NR + r) * kD + c] = o / den;
+    mloc = wave_max(mloc);
+    if (lane == 0) red[wave] = mloc;
+    __syncthreads();
+    const float mmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float dloc = 0.0f;
+    for (int ch = tid; ch < n_chunks; ch += 256) {
+        const float m = wgt[ch];
+        const float w = m == -INFINITY ? 0.0f : __expf(m - mmax);
+        wgt[ch] = w;
+        dloc = __builtin_fmaf(ml[ch * ml_stride + 1], w, dloc);
+    }
+    dloc = wave_sum(dloc);
+    if (lane == 0) red[4 + wave] = dloc;
+    __syncthreads();
+    const float den = red[4] + red[5] + red[6] + red[7];
+    const int cp = tid % 64, slice = tid / 64;
+    const float2* po = reinterpret_cast<const float2*>(part_o + ((size_t)row * max_chunks * NR + r) * kD) + cp;
+    const size_t po_stride = (size_t)NR * kD / 2;
+    float2 o = make_float2(0.f, 0.f);
+    for (int c0 = slice; c0 < n_chunks; c0 += 4 * 8) {
+        float2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int ch = c0 + 4 * u;
+            v[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int ch = c0 + 4 * u;
+            const float w = ch < n_chunks ? wgt[ch] : 0.0f;
+            if (w != 0.0f) {   // a chunk without candidates may hold anything
+                o.x = __builtin_fmaf(v[u].x, w, o.x);
+                o.y = __builtin_fmaf(v[u].y, w, o.y);
+            }
+        }
+    }
+    osum[slice][cp] = o;
+    __syncthreads();
+    if (tid < 64) {
+        const float2 a = osum[0][tid], b = osum[1][tid], c = osum[2][tid], d = osum[3][tid];
+        float2 res;
+        res.x = (a.x + b.x + c.x + d.x) / den;
+        res.y = (a.y + b.y + c.y + d.y) / den;
+        reinterpret_cast<float2*>(out + ((size_t)row * NR + r) * kD)[tid] = res;
+    }
 }
 
 template <int BITS, int GROUP, int G, int NROWS>
@@ -410,7 +562,8 @@ hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* 
         hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, 0, stream, L, A);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(kD), 0, stream, A.part_o, A.part_ml,
+    if (A.n_main + n_extra > kCombineMaxChunks) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(256), 0, stream, A.part_o, A.part_ml,
                        A.max_chunks, A.n_main + n_extra, NR, out);
     return hipGetLastError();
 }

@@ -86,7 +86,9 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
     constexpr int RC = NR > 8 ? 8 : NR;        // rows per multiply-accumulate block
     constexpr int HPD = (32 / BITS) / 4;       // masks per dword
     constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
-    __shared__ float qs_lds[kScoreWaves][2][NR][kD];
+    // +16 floats per half wave: the two halves of a wave read at the same offsets, the pad
+    // puts them in different banks
+    __shared__ float qs_lds[kScoreWaves][2][NR * kD + 16];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, hw = lane >> 5, li = lane & 31;
     const int row = blockIdx.y;
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
 #pragma unroll
             for (int r = 0; r < NR; ++r) {
                 // quad layout: channel c = 16*T + 4*rr + k is word T*16 + k*4 + rr
-                qs_lds[wave][hw][r][(li / 4) * 16 + cc * 4 + (li % 4)] = qsc[r][cc] * sf;
+                qs_lds[wave][hw][r * kD + (li / 4) * 16 + cc * 4 + (li % 4)] = qsc[r][cc] * sf;
                 qz[r] = __builtin_fmaf(qsc[r][cc], z, qz[r]);
             }
         }
@@ -157,7 +159,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
             float4 qv[NR];
 #pragma unroll
             for (int r = 0; r < NR; ++r)
-                qv[r] = *reinterpret_cast<const float4*>(&qs_lds[wave][hw][r][T * 16 + (lane & 3) * 4]);
+                qv[r] = *reinterpret_cast<const float4*>(&qs_lds[wave][hw][r * kD + T * 16 + (lane & 3) * 4]);
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int v = 4 * T + rr, W = v / HPD, h = v % HPD;
