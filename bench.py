@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (3x), the known-size kernel the FETCH_SIZE/WRITE_SIZE "
+                         "counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -63,7 +66,7 @@ def main():
     if args.layers:
         layers = args.layers
     G, D, R = Hq // Hkv, 128, 64
-    total_steps = args.warmup + 2 * args.steps + 2
+    total_steps = args.warmup + 3 * args.steps + 2
     max_seq = ((S + total_steps + 63) // 64 + 1) * 64
     seed = 1000
 
@@ -98,18 +101,16 @@ def main():
     out = [torch.empty((B, Hq, 2, D), dtype=torch.float32, device="cuda") for _ in range(layers)]
     state = {"t": 0}
 
-    def step():
+    def step(gather=True):
         t = state["t"]
         for L in range(layers):
             q = q_all[t % nq_pool, L]
             sc.quantize_append(L, step_k[t], step_v[t], 1, main_s)
             sc.score_topk(L, q, 2, idx[L][t % 2], main_s)
-            if not args.no_gather:
+            if gather and not args.no_gather:
                 sc.gather(L, idx[L][t % 2], (t + 1) % 2, side_s)
             slot = (t % 2) if (t > 0 and not args.no_gather) else -1
             sc.attend(L, q, 2, spec_k, spec_v, slot, out[L], main_s)
-        for bh in sample:   # bookkeeping for the oracle sample (host side, tiny)
-            pass
         state["t"] = t + 1
 
     for _ in range(args.warmup):
@@ -120,6 +121,25 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ---- compute only: the same steps without issuing gathers (attend keeps reading the pairs
+    # ---- staged by the last gather, so its work is unchanged) -----------------------------------
+    compute_ms = None
+    if not args.no_gather:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(gather=False)
+        torch.cuda.synchronize()
+        compute_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # ---- same steps again with an event pair around every kernel phase -------------
     sc.timing(True)
@@ -160,6 +180,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
                    "residual": R, "gather": not args.no_gather},
+        "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "hbm_gbs_layer": round(layer_bytes / (us_layer * 1e-6) / 1e9, 1),
         "kernel_us": breakdown,
         "attend_hbm_gbs": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),

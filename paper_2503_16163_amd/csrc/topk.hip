@@ -8,7 +8,7 @@
 // largest key tau and how many keys equal to tau are still needed; a two-pass
 // ordered compaction then emits every position with key > tau and the first
 // `need` positions with key == tau, in ascending index order (ties go to the
-// lower index).  Rows of up to 32768 keys are held in registers across all
+// lower index).  Rows of up to 65536 keys are held in registers across all
 // passes; longer rows are re-read from L2 in batches of independent loads.
 #include "kernels.h"
 #include "layout.h"
@@ -188,6 +188,8 @@ hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key
         hipLaunchKernelGGL(topk_kernel<8>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
     else if (per_lane <= 32)
         hipLaunchKernelGGL(topk_kernel<32>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
+    else if (per_lane <= 64)
+        hipLaunchKernelGGL(topk_kernel<64>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
     else
         hipLaunchKernelGGL(topk_kernel<0>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
     return hipGetLastError();

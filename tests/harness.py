@@ -72,6 +72,7 @@ class Case:
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R)
         self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
         self.oc = {}
+        self.step_k, self.step_v = [], []
         self.side = torch.cuda.Stream()
         self.idx = [torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)]
         self.step_no = 0
@@ -102,8 +103,8 @@ class Case:
         self.sc.quantize_append(0, to_dev(kb, self.dtype), to_dev(vb, self.dtype), 1)
         for (b, h) in self.sample:
             self.oc[(b, h)].append(kb[b, h], vb[b, h])
-        self.k_bits = np.concatenate([self.k_bits, kb], axis=2)
-        self.v_bits = np.concatenate([self.v_bits, vb], axis=2)
+        self.step_k.append(kb)
+        self.step_v.append(vb)
 
     # ---- checks -------------------------------------------------------------
     def check_quantized(self):
@@ -125,8 +126,12 @@ class Case:
         n, _ = self.sc.counts(0)
         count = n - first if count is None else count
         rows = self.sc.export_rows(0, first, count)
-        assert np.array_equal(rows[:, :, :, 0], self.k_bits[:, :, first:first + count])
-        assert np.array_equal(rows[:, :, :, 1], self.v_bits[:, :, first:first + count])
+        k_all = np.concatenate([self.k_bits[:, :, first:]] + self.step_k, axis=2) if first < self.S else \
+            np.concatenate(self.step_k, axis=2)[:, :, first - self.S:]
+        v_all = np.concatenate([self.v_bits[:, :, first:]] + self.step_v, axis=2) if first < self.S else \
+            np.concatenate(self.step_v, axis=2)[:, :, first - self.S:]
+        assert np.array_equal(rows[:, :, :, 0], k_all[:, :, :count])
+        assert np.array_equal(rows[:, :, :, 1], v_all[:, :, :count])
 
     def decode_step(self, use_spec=True, check_logits=True, do_gather=True):
         """score_topk -> gather(next slot) -> attend(current slot), each checked against the oracle."""

@@ -154,3 +154,36 @@ def test_error_paths():
         with pytest.raises(binding.SpeCacheError) as ei:
             binding.SpeCache(**base)
         assert ei.value.code == binding.EINVAL
+
+
+# ---- the benchmark's full sizes, in the launch configuration bench.py times; the oracle mirrors a
+# ---- sample of (batch, KV head) rows, all of whose outputs are compared element by element.
+FULL = {
+    "config2": dict(B=1, Hq=32, Hkv=32, S=16384, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 0), (0, 13), (0, 31)]),
+    "M0_7B_32k": dict(B=1, Hq=32, Hkv=32, S=32768, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 5), (0, 30)]),
+    "config3": dict(B=16, Hq=32, Hkv=32, S=2048, dtype=synth.FP16, bits=2, g=32, k=128,
+                    sample=[(0, 0), (7, 19), (15, 31), (3, 8)]),
+    "config4": dict(B=4, Hq=32, Hkv=8, S=32768, dtype=synth.BF16, bits=2, g=64, k=512, sample=[(1, 2), (3, 7)]),
+    "config5": dict(B=1, Hq=32, Hkv=8, S=131072, dtype=synth.BF16, bits=1, g=32, k=1024, sample=[(0, 6)]),
+}
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_sampled(name):
+    from tests.harness import Case
+    kw = dict(FULL[name])
+    sample = kw.pop("sample")
+    c = Case(kw["B"], kw["Hq"], kw["Hkv"], kw["S"], kw["dtype"], kw["bits"], kw["g"], kw["k"], seed=3000 + kw["S"],
+             sample=sample)
+    try:
+        c.load()
+        c.check_quantized()
+        c.check_offload(first=kw["S"] - 70, count=70)
+        for t in range(2):
+            c.append_token(t)
+            c.decode_step(check_logits=(t == 0))
+        c.check_offload(first=kw["S"], count=2)
+        print(name, c.stats)
+    finally:
+        c.close()
