@@ -3,17 +3,23 @@
 // All sizes are per (batch, KV head) "row" of a layer; head_dim D = 128.
 //
 // K codes (keys are grouped per channel over g tokens; Section 2.1 / 4.1):
-//   blocks of 32 tokens, each block = BITS planes of [32 tokens][16 bytes].
-//   A token's 128 codes occupy 4*BITS dwords; dword W (W = 4*plane + d) holds
-//   the 32/BITS channels c with c / (32/BITS) == W.  Inside a dword the code of
-//   channel c sits at bit 8*(w % 4) + BITS*(w / 4), w = c % (32/BITS): masking
-//   with (2^BITS - 1) * 0x01010101 << BITS*h leaves four codes, one per byte,
-//   each scaled by 2^(BITS*h); v_cvt_f32_ubyte{0..3} turns them into floats and
-//   the power of two is folded into the multiplier.  Byte b of that mask is
-//   channel 4*h + b of the dword, i.e. channel % 4 == b.
-//   A wave reads a plane of a block as 32 lanes x 16 B = 512 contiguous bytes.
-// K metadata: [token group j][channel c] one dword = min | max << 16 (16-bit
-//   patterns of the cache dtype); scale and zero-point are derived on use.
+//   tiles of 512 tokens = 16 sub-groups of 32 tokens.  A token's 128 codes occupy
+//   4*BITS dwords; dword W holds the 32/BITS channels c with c / (32/BITS) == W.  A tile
+//   is laid out as [dword W][2 halves][64 lanes][16 bytes]: lane = 4*G + k for sub-group
+//   G and quad lane k, and the lane's 16 bytes in half hf are dword W of its tokens
+//   32*G + 8*k + 4*hf + {0,1,2,3}.  The scoring wave owns a tile and walks W: each lane
+//   scores the 8 consecutive tokens 8*k .. 8*k+7 of one sub-group, every load is 1 KB
+//   contiguous across the wave, and the four lanes of a quad share one group's
+//   multipliers.  Inside a dword the code of channel c sits at bit
+//   8*(w % 4) + BITS*(w / 4), w = c % (32/BITS): masking with
+//   (2^BITS - 1) * 0x01010101 << BITS*h leaves four codes, one per byte, each scaled by
+//   2^(BITS*h); v_cvt_f32_ubyte{0..3} turns them into floats and the power of two is
+//   folded into the multiplier.  Byte b of that mask is channel 4*h + b of the dword,
+//   i.e. channel % 4 == b.
+// K metadata: per token group j, 128 dwords = min | max << 16 (16-bit patterns of the
+//   cache dtype), stored as [channel % 4][channel / 4] so that the quad lane k = c % 4
+//   reads the channels it multiplies as consecutive dwords; scale and zero-point are
+//   derived on use.
 // V codes (values are grouped per token over g channels):
 //   blocks of 32 tokens, each block = [2 halves of 16 tokens][16*BITS lanes][16 B];
 //   byte t of a lane's 16 bytes is token 16*half + t and holds the 8/BITS
@@ -30,9 +36,11 @@ namespace specache {
 
 constexpr int kD = 128;          // head_dim
 constexpr int kRowBytes = 512;   // one 16-bit (K,V) pair
-constexpr int kBlockTokens = 32; // tokens per code block
+constexpr int kBlockTokens = 32; // tokens per V code block / per K sub-group
+constexpr int kTileTokens = 512; // tokens per K code tile
 
 __host__ __device__ constexpr int code_block_bytes(int bits) { return 512 * bits; }
+__host__ __device__ constexpr int k_tile_bytes(int bits) { return kTileTokens * 16 * bits; }
 
 // ---- 16-bit -> float, exact --------------------------------------------------
 template <bool BF16>
@@ -85,9 +93,12 @@ __host__ __device__ __forceinline__ int k_bit_of_channel(int c) {
 // byte offset, inside a row's K code area, of dword W of token t
 template <int BITS>
 __host__ __device__ __forceinline__ size_t k_dword_offset(int t, int W) {
-    const int blk = t / kBlockTokens, tok = t % kBlockTokens, plane = W / 4, d = W % 4;
-    return (size_t)blk * code_block_bytes(BITS) + (size_t)plane * 512 + (size_t)tok * 16 + (size_t)d * 4;
+    const int tile = t / kTileTokens, u = t % kTileTokens;
+    const int lane = 4 * (u / 32) + (u % 32) / 8, slot = u % 8;
+    return (size_t)tile * k_tile_bytes(BITS) + ((size_t)(W * 2 + slot / 4) * 64 + lane) * 16 + (size_t)(slot % 4) * 4;
 }
+// dword index, inside a token group's 128 metadata dwords, of channel c
+__host__ __device__ __forceinline__ int k_meta_index(int c) { return (c % 4) * 32 + c / 4; }
 
 // ---- V code addressing ---------------------------------------------------------
 template <int BITS>

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(128) void flush_kernel(LayerView L, const uint16_t*
     derive_scale_zero<BITS>(mn, mx, s, z);
 #pragma unroll
     for (int e = 0; e < G; ++e) kcode[e][c] = (uint8_t)quantize_one<BITS>(kx[e], s, z);
-    L.km[(size_t)row * L.km_stride + (size_t)(t0 / G) * kD + c] = narrow16<BF16>(mn) | (narrow16<BF16>(mx) << 16);
+    L.km[(size_t)row * L.km_stride + (size_t)(t0 / G) * kD + k_meta_index(c)] = narrow16<BF16>(mn) | (narrow16<BF16>(mx) << 16);
     __syncthreads();
 
     // values: G tokens x M groups = 128 (token, group) pairs, one per thread
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(128) void export_kernel(LayerView L, int Nq, uint8_
     }
     if (t % G == 0) {
         const size_t gi = ((size_t)row * (Nq / G) + t / G) * kD + c;
-        const uint32_t m = L.km[(size_t)row * L.km_stride + (size_t)(t / G) * kD + c];
+        const uint32_t m = L.km[(size_t)row * L.km_stride + (size_t)(t / G) * kD + k_meta_index(c)];
         if (k_mnmx) { k_mnmx[2 * gi] = (uint16_t)(m & 0xFFFFu); k_mnmx[2 * gi + 1] = (uint16_t)(m >> 16); }
         if (k_sz) {
             float s, z;

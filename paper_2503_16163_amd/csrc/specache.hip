@@ -190,8 +190,8 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
         LayerView& v = L.view;
         v.rows = rows; v.G = G; v.bits = c.bits; v.group = c.group; v.R = c.residual;
         v.max_seq = c.max_seq; v.topk = c.topk; v.bf16 = c.dtype == SPECACHE_BF16;
-        v.kc_stride = cap / kBlockTokens * code_block_bytes(c.bits);
-        v.vc_stride = v.kc_stride;
+        v.kc_stride = (cap + kTileTokens - 1) / kTileTokens * k_tile_bytes(c.bits);
+        v.vc_stride = cap / kBlockTokens * code_block_bytes(c.bits);
         v.km_stride = cap / c.group * kD;
         v.vm_stride = cap * (kD / c.group);
         SPC_ALLOC(hipMalloc((void**)&v.kc, rows * v.kc_stride));
