@@ -2,67 +2,89 @@
 // "Pre-decoding" for the single-row case).  Softmax is monotone, so the selection
 // runs on the logits' order-preserving integer keys.
 //
-// One workgroup of 1024 threads per (batch, KV head).  Exact radix select on the
-// 32-bit keys above a cheap lower bound, most significant digit first (11 + 11 + 10
-// bits), gives the k-th
-// largest key tau and how many keys equal to tau are still needed; a two-pass
-// ordered compaction then emits every position with key > tau and the first
-// `need` positions with key == tau, in ascending index order (ties go to the
-// lower index).  Rows of up to 65536 keys are held in registers across all
-// passes; longer rows are re-read from L2 in batches of independent loads.
+// One workgroup of 1024 threads per (batch, KV head); rows of up to 65536 keys sit in
+// registers, longer rows are re-read from L2 in batches of independent loads.  The
+// number of barrier-separated phases, not arithmetic, bounds this kernel, so the exact
+// k-th largest key tau is found in three short steps:
+//   1. floor: every thread's largest key is a distinct element of the row, so tau is at
+//      least the k-th largest thread maximum; one 2048-bin histogram of the maxima's
+//      leading bits gives a floor F below which nothing can be selected;
+//   2. one 2048-bin histogram of (key - F) >> shift over the keys >= F, with the shift
+//      chosen from the row maximum so that the bins are as fine as 2048 bins allow,
+//      locates the bin that holds tau and the rank of tau inside it;
+//   3. the handful of keys in that bin are collected and ranked by one wave.
+// If that bin holds more than 64 keys (many equal or almost equal scores) step 2 is
+// repeated inside the bin, which narrows the range by 11 bits each time.
+// A two-pass ordered compaction then emits every position with key > tau and the first
+// `need` positions with key == tau in ascending index order (ties to the lower index).
 #include "kernels.h"
 #include "layout.h"
 
 namespace specache {
 namespace {
 
-constexpr int kTopkThreads = 1024;
-constexpr int kTopkWaves = kTopkThreads / 64;
 constexpr int kBins = 2048;
-constexpr int kBatch = 8;   // key loads in flight per thread
+constexpr int kBatch = 8;    // key loads in flight per thread (streaming variant)
+constexpr int kSmall = 64;   // keys one wave ranks directly
 
 // exclusive prefix of a 64-bit ballot below this lane
 __device__ __forceinline__ int prefix_below(unsigned long long mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
-// Digit selection shared by both kernels: given hist[] of the current digit among the
-// keys that match the prefix so far, find the digit holding the need-th largest key.
-__device__ __forceinline__ void select_digit(const uint32_t* hist, uint32_t* wave_sum, uint32_t* sel, uint32_t need) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    // thread t owns bins 2t, 2t+1; "greater" count of a bin = total - inclusive prefix
-    const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-    uint32_t incl = h0 + h1;
+// hist[] is stored skewed (bin b at b + b / 32) so that a lane walking 32 consecutive bins
+// and its neighbours touch different banks.
+__device__ __forceinline__ int skew(int b) { return b + (b >> 5); }
+constexpr int kHistWords = kBins + kBins / 32;
+
+// Wave 0 only: find the bin holding the need-th largest counted key (bins ordered by
+// value, larger bin = larger keys).  Writes sel[0] = bin (or 0xFFFFFFFF if fewer than
+// `need` keys were counted) and sel[1] = rank of the wanted key inside that bin (1-based,
+// counted from the bin's largest key).
+__device__ __forceinline__ void select_bin_wave0(const uint32_t* hist, uint32_t* sel, uint32_t need) {
+    const int lane = threadIdx.x & 63;
+    // lane l owns bins 32l .. 32l+31, held in registers
+    uint32_t h[32];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        h[j] = hist[skew(32 * lane + j)];
+        mine += h[j];
+    }
+    // keys in bins owned by higher lanes
+    uint32_t above = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += o;
+        const uint32_t o = __shfl_down(above, d, 64);
+        if (lane + d < 64) above += o;
     }
-    if (lane == 63) wave_sum[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0, total = 0;
-    for (int w = 0; w < kTopkWaves; ++w) {
-        const uint32_t s = wave_sum[w];
-        if (w < wave) base += s;
-        total += s;
+    above -= mine;
+    if (lane == 0) sel[0] = 0xFFFFFFFFu;
+    // walk this lane's bins from the top; exactly one (lane, bin) pair brackets `need`
+    uint32_t gt = above, found_bin = 0xFFFFFFFFu, found_rank = 0;
+#pragma unroll
+    for (int j = 31; j >= 0; --j) {
+        const bool hit = gt < need && need <= gt + h[j];
+        found_bin = hit ? (uint32_t)(32 * lane + j) : found_bin;
+        found_rank = hit ? need - gt : found_rank;
+        gt += h[j];
     }
-    incl += base;                                  // keys in bins <= 2t+1
-    const uint32_t gt1 = total - incl;             // keys in bins > 2t+1
-    const uint32_t gt0 = gt1 + h1;                 // keys in bins > 2t
-    if (gt1 < need && need <= gt1 + h1) { sel[0] = 2 * tid + 1; sel[1] = need - gt1; }
-    if (gt0 < need && need <= gt0 + h0) { sel[0] = 2 * tid; sel[1] = need - gt0; }
-    __syncthreads();
+    if (found_bin != 0xFFFFFFFFu) { sel[0] = found_bin; sel[1] = found_rank; }
 }
 
-// KPT > 0: the row fits in registers (KPT keys per lane, wave w owning the contiguous
-// index range [w*seg, (w+1)*seg)), read once.  KPT == 0: any length, keys re-read from
-// L2 in batches of independent loads on every pass.
-template <int KPT>
-__global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const uint32_t* __restrict__ keys,
-                                                            size_t key_stride, int32_t* __restrict__ idx_out) {
-    __shared__ uint32_t hist[kBins];
-    __shared__ uint32_t wave_sum[kTopkWaves];
+// THREADS: 1024 for long rows; 256 for rows of up to 8192 keys, so that several rows share a
+// compute unit and hide each other's barrier latency.
+template <int THREADS, int KPT>
+__global__ __launch_bounds__(THREADS) void topk_kernel(int Nq, int k, const uint32_t* __restrict__ keys,
+                                                       size_t key_stride, int32_t* __restrict__ idx_out) {
+    constexpr int kTopkThreads = THREADS;
+    constexpr int kTopkWaves = THREADS / 64;
+    __shared__ uint32_t hist[kHistWords];
+    __shared__ uint32_t wave_red[kTopkWaves];
     __shared__ uint32_t sel[2];
+    __shared__ uint32_t small_keys[kSmall];
+    __shared__ uint32_t small_n;
+    __shared__ uint32_t result[2];     // tau, number of keys == tau to take
     __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
 
     const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -72,7 +94,12 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const
 
     for (int j = keff + tid; j < k; j += kTopkThreads) out[j] = -1;
     if (keff == 0) return;
+    if (keff == Nq) {   // everything is selected
+        for (int j = tid; j < Nq; j += kTopkThreads) out[j] = j;
+        return;
+    }
 
+    // wave w owns the contiguous index range [w*seg, (w+1)*seg), seg a multiple of 64
     const int seg = ((Nq + kTopkWaves * 64 - 1) / (kTopkWaves * 64)) * 64;
     const int lo = wave * seg, hi = (lo + seg < Nq) ? lo + seg : Nq;
 
@@ -84,7 +111,10 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const
             key[it] = i < hi ? kr[i] : 0u;
         }
     }
-    // apply f(index, key) to every key slot of this thread (slots with index >= hi are padding)
+    // apply f(index, key) to every key slot of this thread.  Slots with index >= hi are padding
+    // and hold key 0; every range tested below starts at 1 or above, so padding never matches
+    // and no pass needs an index test.  (Key 0 itself is the one NaN pattern 0xFFFFFFFF; it is
+    // treated as below every other score.)
     auto for_each_key = [&](auto&& f) {
         if constexpr (KPT > 0) {
 #pragma unroll
@@ -102,62 +132,100 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const
             }
         }
     };
-    auto clear_hist = [&]() {
-        for (int b = tid; b < kBins; b += kTopkThreads) hist[b] = 0;
-        __syncthreads();
-    };
 
-    // ---- a lower bound that leaves few candidates ------------------------------------
-    // Every thread's largest key is a distinct element of the row, so the keff-th largest
-    // key overall is at least the keff-th largest of the thread maxima; their leading
-    // 11-bit digit gives a floor below which no key can be selected.  LDS atomics then
-    // only see the few keys above the floor instead of the whole row.
-    uint32_t floor_key = 0;
+    // ---- step 1: row maximum and the floor from the thread maxima ---------------------
+    uint32_t tmax = 0;
+    for_each_key([&](int, uint32_t kv) { tmax = kv > tmax ? kv : tmax; });
+    const bool any = lo + lane < hi;   // this thread holds at least one key
     {
-        uint32_t tmax = 0;
-        bool any = false;
-        for_each_key([&](int i, uint32_t kv) {
-            if (i < hi) { tmax = kv > tmax ? kv : tmax; any = true; }
-        });
-        clear_hist();
-        if (any) atomicAdd(&hist[tmax >> 21], 1u);
-        if (tid == 0) sel[0] = 0xFFFFFFFFu;   // stays if fewer than keff threads hold keys
-        __syncthreads();
-        select_digit(hist, wave_sum, sel, (uint32_t)keff);
-        if (sel[0] != 0xFFFFFFFFu) floor_key = sel[0] << 21;
-        __syncthreads();
-    }
-
-    // ---- radix select among keys >= floor_key: tau and how many keys == tau to take --
-    uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)keff;
-    constexpr int shifts[3] = {21, 10, 0};
-    constexpr int widths[3] = {11, 11, 10};
+        uint32_t wm = tmax;
 #pragma unroll
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = shifts[pass];
-        const uint32_t nb = 1u << widths[pass];
-        clear_hist();
-        const uint32_t cand_lo = prefix > floor_key ? prefix : floor_key;   // no key below this can match
-        for_each_key([&](int i, uint32_t kv) {
-            const bool cand = i < hi && kv >= cand_lo;
-            if (__ballot(cand) == 0) return;   // wave-uniform: most key slots hold no candidate
-            if (cand && (kv & prefix_mask) == prefix) atomicAdd(&hist[(kv >> shift) & (nb - 1)], 1u);
+        for (int m = 32; m >= 1; m >>= 1) { const uint32_t o = __shfl_xor(wm, m, 64); wm = o > wm ? o : wm; }
+        if (lane == 0) wave_red[wave] = wm;
+    }
+    for (int b = tid; b < kHistWords; b += kTopkThreads) hist[b] = 0;
+    __syncthreads();
+    uint32_t row_max = 0;
+#pragma unroll
+    for (int w = 0; w < kTopkWaves; ++w) row_max = wave_red[w] > row_max ? wave_red[w] : row_max;
+    if (any) atomicAdd(&hist[skew(tmax >> 21)], 1u);
+    __syncthreads();
+    if (wave == 0) select_bin_wave0(hist, sel, (uint32_t)keff);
+    __syncthreads();
+    // fewer than keff threads hold keys: no floor
+    uint32_t range_lo = sel[0] == 0xFFFFFFFFu ? 1u : (sel[0] << 21);
+    range_lo = range_lo < 1u ? 1u : range_lo;
+    uint32_t range_hi = row_max;          // inclusive
+    uint32_t need = (uint32_t)keff;       // rank of tau among the keys >= range_lo
+    __syncthreads();
+
+    // ---- step 2 (repeated while the bin is crowded): histogram inside [range_lo, range_hi] ----
+    for (int round = 0; round < 4; ++round) {
+        const uint32_t span = range_hi - range_lo;
+        const int shift = span < (uint32_t)kBins ? 0 : 32 - __builtin_clz(span) - 11;
+        for (int b = tid; b < kHistWords; b += kTopkThreads) hist[b] = 0;
+        if (tid == 0) small_n = 0;
+        __syncthreads();
+        for_each_key([&](int, uint32_t kv) {
+            const uint32_t off = kv - range_lo;
+            const bool cand = off <= span;       // one unsigned test for range_lo <= kv <= range_hi
+            if (__ballot(cand) == 0) return;     // wave-uniform: most key slots hold no candidate
+            if (cand) atomicAdd(&hist[skew(off >> shift)], 1u);
         });
         __syncthreads();
-        select_digit(hist, wave_sum, sel, need);
-        prefix |= sel[0] << shift;
-        prefix_mask |= (nb - 1) << shift;
-        need = sel[1];
+        if (wave == 0) select_bin_wave0(hist, sel, need);
+        __syncthreads();
+        const uint32_t bin = sel[0], rank = sel[1];
+        const uint32_t bin_lo = range_lo + (bin << shift);
+        const uint32_t bin_hi = shift == 0 ? bin_lo : bin_lo + ((1u << shift) - 1u);
+        const uint32_t in_bin = hist[skew(bin)];
+        if (shift == 0) {                  // the bin is a single key value
+            if (tid == 0) { result[0] = bin_lo; result[1] = rank; }
+            __syncthreads();
+            break;
+        }
+        if (in_bin <= (uint32_t)kSmall) {
+            // ---- step 3: one wave ranks the bin's keys ----
+            for_each_key([&](int, uint32_t kv) {
+                const bool cand = kv - bin_lo <= bin_hi - bin_lo;
+                if (__ballot(cand) == 0) return;
+                if (cand) small_keys[atomicAdd(&small_n, 1u)] = kv;
+            });
+            __syncthreads();
+            if (wave == 0) {
+                const uint32_t n = small_n;
+                const uint32_t mine = lane < (int)n ? small_keys[lane] : 0u;
+                uint32_t greater = 0, equal = 0;
+#pragma unroll
+                for (int j = 0; j < kSmall; ++j) {
+                    const uint32_t kj = __builtin_amdgcn_readlane(mine, j);   // lane j's key, wave-uniform
+                    const bool live = (uint32_t)j < n;
+                    greater += live && kj > mine;
+                    equal += live && kj == mine;
+                }
+                // tau is the key with greater < rank <= greater + equal
+                if (lane < (int)n && greater < rank && rank <= greater + equal) {
+                    result[0] = mine;
+                    result[1] = rank - greater;
+                }
+            }
+            __syncthreads();
+            break;
+        }
+        range_lo = bin_lo;
+        range_hi = bin_hi;
+        need = rank;
         __syncthreads();
     }
-    const uint32_t tau = prefix;
+    const uint32_t tau = result[0];
+    need = result[1];
 
     // ---- ordered compaction: count per wave, then emit in index order ---------------
     uint32_t cnt_gt = 0, cnt_eq = 0;
-    for_each_key([&](int i, uint32_t kv) {
-        const unsigned long long mge = __ballot(i < hi && kv >= tau);
+    for_each_key([&](int, uint32_t kv) {
+        const unsigned long long mge = __ballot(kv >= tau);
         if (mge == 0) return;              // wave-uniform skip
-        const unsigned long long me = __ballot(i < hi && kv == tau);
+        const unsigned long long me = __ballot(kv == tau);
         cnt_gt += __popcll(mge & ~me);
         cnt_eq += __popcll(me);
     });
@@ -166,8 +234,8 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const
     uint32_t gt_before = 0, eq_before = 0;
     for (int w = 0; w < wave; ++w) { gt_before += wave_gt[w]; eq_before += wave_eq[w]; }
     for_each_key([&](int i, uint32_t kv) {
-        if (__ballot(i < hi && kv >= tau) == 0) return;   // wave-uniform skip
-        const bool gt = i < hi && kv > tau, eq = i < hi && kv == tau;
+        if (__ballot(kv >= tau) == 0) return;   // wave-uniform skip
+        const bool gt = kv > tau, eq = kv == tau;
         const unsigned long long mg = __ballot(gt), me = __ballot(eq);
         const uint32_t my_eq_rank = eq_before + prefix_below(me);
         if (gt || (eq && my_eq_rank < need)) {
@@ -183,15 +251,14 @@ __global__ __launch_bounds__(kTopkThreads) void topk_kernel(int Nq, int k, const
 
 hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
                        hipStream_t stream) {
-    const int per_lane = (Nq + kTopkThreads - 1) / kTopkThreads;   // keys per lane if the row sits in registers
-    if (per_lane <= 8)
-        hipLaunchKernelGGL(topk_kernel<8>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
-    else if (per_lane <= 32)
-        hipLaunchKernelGGL(topk_kernel<32>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
-    else if (per_lane <= 64)
-        hipLaunchKernelGGL(topk_kernel<64>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
-    else
-        hipLaunchKernelGGL(topk_kernel<0>, dim3(rows), dim3(kTopkThreads), 0, stream, Nq, k, keys, key_stride, idx_out);
+    const int per_lane_256 = (Nq + 255) / 256, per_lane = (Nq + 1023) / 1024;   // keys per lane held in registers
+#define SPC_TOPK(T, K) hipLaunchKernelGGL((topk_kernel<T, K>), dim3(rows), dim3(T), 0, stream, Nq, k, keys, key_stride, idx_out)
+    if (per_lane_256 <= 8) SPC_TOPK(256, 8);
+    else if (per_lane_256 <= 32) SPC_TOPK(256, 32);
+    else if (per_lane <= 32) SPC_TOPK(1024, 32);
+    else if (per_lane <= 64) SPC_TOPK(1024, 64);
+    else SPC_TOPK(1024, 0);
+#undef SPC_TOPK
     return hipGetLastError();
 }
 
