@@ -40,15 +40,30 @@ __device__ __forceinline__ float cvt_ubyte(uint32_t w) {
 
 __device__ __forceinline__ uint32_t comp(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
+// Wave-wide reductions on the VALU: four DPP steps leave every lane with its 16-lane row's
+// result, the four row results are then read as scalars.  (A butterfly of ds_bpermute
+// shuffles costs an LDS round trip per step.)
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
-    return v;
+    v = fmaxf(v, dpp_move<kDppXor1>(v));
+    v = fmaxf(v, dpp_move<kDppXor2>(v));
+    v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
+    v = fmaxf(v, dpp_move<kDppMirror>(v));
+    return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    return v;
+    v += dpp_move<kDppXor1>(v);
+    v += dpp_move<kDppXor2>(v);
+    v += dpp_move<kDppHalfMirror>(v);
+    v += dpp_move<kDppMirror>(v);
+    return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 
 struct AttendArgs {
@@ -132,20 +147,26 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     // consecutive cells, and the pad spreads those over distinct banks.
     constexpr int kCell = 16 * NR + 4;
     constexpr int kLg = NR * CHX, kPs = (CH / 16) * M * kCell, kOl = kWaves * NR * kD;
-    constexpr int kRegion = kLg > kPs ? (kLg > kOl ? kLg : kOl) : (kPs > kOl ? kPs : kOl);
+    // the extra chunks' tables (query rows, candidate pointers) live behind lg in the same region:
+    // a workgroup is either a main or an extra chunk, and LDS per workgroup decides how many
+    // chunks are resident per compute unit
+    constexpr int kXq = NR * kD, kXp = 2 * kExtraChunk * 2 /* two pointer tables, 8 B each */, kXs = kExtraChunk / 4;
+    constexpr int kExtra = kLg + kXq + kXp + kXs;
+    constexpr int kMax1 = kExtra > kPs ? kExtra : kPs;
+    constexpr int kRegion = kMax1 > kOl ? kMax1 : kOl;
     __shared__ __attribute__((aligned(16))) float smem[kRegion];
     __shared__ float red[kWaves * NR * (1 + M)];
     __shared__ float red_sum[kWaves * NR];
     __shared__ float red_z[kWaves * NR * M];
     __shared__ uint32_t maskbits[CH / 32];
-    __shared__ float qf[NR][kD];
-    __shared__ const uint16_t* src_k[kExtraChunk];
-    __shared__ const uint16_t* src_v[kExtraChunk];
-    __shared__ bool src_spec[kExtraChunk];
 
     float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
     float* ps = smem;                        // [CH/16][M] cells
     float* o_lds = smem;                     // [kWaves][NR][128]
+    float (*qf)[kD] = reinterpret_cast<float (*)[kD]>(smem + kLg);
+    const uint16_t** src_k = reinterpret_cast<const uint16_t**>(smem + kLg + kXq);
+    const uint16_t** src_v = src_k + kExtraChunk;
+    bool* src_spec = reinterpret_cast<bool*>(smem + kLg + kXq + kXp);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int row = blockIdx.y, chunk = blockIdx.x;
@@ -488,6 +509,9 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 // Merge the chunk partials of one (KV head, query row): o = sum_c o_c e^(m_c - m) / sum_c l_c e^(m_c - m).
 // 256 threads = 4 slices of the chunk list x 64 channel pairs; the chunk weights are
 // computed once into LDS so that the partial-output loads are independent of each other.
+// (Folding this into the partial kernel behind a "last workgroup" counter needs a
+// device-scope fence in every workgroup, which writes back and invalidates the L2 of
+// its XCD; measured, that made the kernel eight times slower than this extra launch.)
 constexpr int kCombineMaxChunks = 1280;
 __global__ __launch_bounds__(256) void attend_combine_kernel(const float* __restrict__ part_o,
                                                              const float* __restrict__ part_ml, int max_chunks,
@@ -555,6 +579,7 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* __rest
 template <int BITS, int GROUP, int G, int NROWS>
 hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* out, hipStream_t stream) {
     constexpr int NR = G * NROWS;
+    if (A.n_main + n_extra > kCombineMaxChunks) return hipErrorInvalidValue;
     const dim3 grid(A.n_main + n_extra, L.rows), block(kThreads);
     if (L.bf16)
         hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, true>), grid, block, 0, stream, L, A);
@@ -562,7 +587,6 @@ hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* 
         hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, 0, stream, L, A);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (A.n_main + n_extra > kCombineMaxChunks) return hipErrorInvalidValue;
     hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(256), 0, stream, A.part_o, A.part_ml,
                        A.max_chunks, A.n_main + n_extra, NR, out);
     return hipGetLastError();
