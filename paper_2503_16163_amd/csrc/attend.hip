@@ -153,7 +153,11 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     constexpr int kXq = NR * kD, kXp = 2 * kExtraChunk * 2 /* two pointer tables, 8 B each */, kXs = kExtraChunk / 4;
     constexpr int kExtra = kLg + kXq + kXp + kXs;
     constexpr int kMax1 = kExtra > kPs ? kExtra : kPs;
-    constexpr int kRegion = kMax1 > kOl ? kMax1 : kOl;
+    // with more than four query rows the value loop runs in passes of four rows and the merged
+    // outputs need LDS of their own while ps is still in use
+    constexpr bool kSplit = NR > 4;
+    constexpr int RH = kSplit ? 4 : NR;
+    constexpr int kRegion = kSplit ? kMax1 + kOl : (kMax1 > kOl ? kMax1 : kOl);
     __shared__ __attribute__((aligned(16))) float smem[kRegion];
     __shared__ float red[kWaves * NR * (1 + M)];
     __shared__ float red_sum[kWaves * NR];
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 
     float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
     float* ps = smem;                        // [CH/16][M] cells
-    float* o_lds = smem;                     // [kWaves][NR][128]
+    float* o_lds = kSplit ? smem + kMax1 : smem;   // [kWaves][NR][128]
     float (*qf)[kD] = reinterpret_cast<float (*)[kD]>(smem + kLg);
     const uint16_t** src_k = reinterpret_cast<const uint16_t**>(smem + kLg + kXq);
     const uint16_t** src_v = src_k + kExtraChunk;
@@ -204,9 +208,6 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 meta[tt][0] = t2.x; meta[tt][1] = t2.y;
             }
         }
-        uint4 w4 = make_uint4(0, 0, 0, 0);
-        if (tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
-
         // prefetched positions of this chunk, as a bitmap
         if (tid < CH / 32) maskbits[tid] = 0u;
         __syncthreads();
@@ -295,81 +296,71 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             l_row[r] = v;
         }
 
-        // sum_i (p_i s_i) code[i][c] for this lane's CPB channels
-        float acc[CPB][NR];
-#pragma unroll
-        for (int j = 0; j < CPB; ++j)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) acc[j][r] = 0.0f;
-        for (int u = tid; u < units; u += kThreads) {
-            const int blk = u / LPB;
-            uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
-            if (u + kThreads < units)
-                w4n = *reinterpret_cast<const uint4*>(vc_lane + (size_t)((u + kThreads) / LPB) * code_block_bytes(BITS));
-            const int hb = blk * 2 + within / (16 * BITS);   // 16-token half block inside the chunk
-            const float* psb = ps + (hb * M + mgrp) * kCell;
-#pragma unroll
-            for (int dq = 0; dq < 4; ++dq) {
-                const uint32_t w = comp(w4, dq);
-                float pv[4][NR];
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-#pragma unroll
-                    for (int r = 0; r < NR; ++r) pv[b][r] = psb[(dq * 4 + b) * NR + r];
-#pragma unroll
-                for (int j = 0; j < CPB; ++j) {
-                    const uint32_t mk = w & (MASK << (BITS * j));
-                    const float f0 = cvt_ubyte<0>(mk), f1 = cvt_ubyte<1>(mk), f2 = cvt_ubyte<2>(mk), f3 = cvt_ubyte<3>(mk);
-#pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        acc[j][r] = __builtin_fmaf(f0, pv[0][r], acc[j][r]);
-                        acc[j][r] = __builtin_fmaf(f1, pv[1][r], acc[j][r]);
-                        acc[j][r] = __builtin_fmaf(f2, pv[2][r], acc[j][r]);
-                        acc[j][r] = __builtin_fmaf(f3, pv[3][r], acc[j][r]);
-                    }
-                }
-            }
-            w4 = w4n;
-        }
-        // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
-#pragma unroll
-        for (int j = 0; j < CPB; ++j)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                float v = acc[j][r] * __uint_as_float((uint32_t)(127 - BITS * j) << 23);
-#pragma unroll
-                for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
-                acc[j][r] = v;
-            }
-        float zsum[NR][M];   // read before the region is reused
-#pragma unroll
-        for (int r = 0; r < NR; ++r)
-#pragma unroll
-            for (int m = 0; m < M; ++m) {
-                float v = 0.0f;
-                for (int w = 0; w < kWaves; ++w) v += red_z[(w * NR + r) * M + m];
-                zsum[r][m] = v;
-            }
-        __syncthreads();   // everyone is done with lg / ps
-        if (lane < 16 * BITS) {
+        // sum_i (p_i s_i) code[i][c] for this lane's CPB channels, RH query rows per pass (with
+        // more than four rows the accumulators of all rows at once would halve the occupancy)
+        for (int r0 = 0; r0 < NR; r0 += RH) {
+            float acc[CPB][RH];
 #pragma unroll
             for (int j = 0; j < CPB; ++j)
 #pragma unroll
-                for (int r = 0; r < NR; ++r) o_lds[((size_t)wave * NR + r) * kD + Lc * CPB + j] = acc[j][r];
+                for (int r = 0; r < RH; ++r) acc[j][r] = 0.0f;
+            uint4 w4 = make_uint4(0, 0, 0, 0);
+            if (tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
+            for (int u = tid; u < units; u += kThreads) {
+                const int blk = u / LPB;
+                uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
+                if (u + kThreads < units)
+                    w4n = *reinterpret_cast<const uint4*>(vc_lane + (size_t)((u + kThreads) / LPB) * code_block_bytes(BITS));
+                const int hb = blk * 2 + within / (16 * BITS);   // 16-token half block inside the chunk
+                const float* psb = ps + (hb * M + mgrp) * kCell + r0;
+#pragma unroll
+                for (int dq = 0; dq < 4; ++dq) {
+                    const uint32_t w = comp(w4, dq);
+                    float pv[4][RH];
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+#pragma unroll
+                        for (int r = 0; r < RH; ++r) pv[b][r] = psb[(dq * 4 + b) * NR + r];
+#pragma unroll
+                    for (int j = 0; j < CPB; ++j) {
+                        const uint32_t mk = w & (MASK << (BITS * j));
+                        const float f0 = cvt_ubyte<0>(mk), f1 = cvt_ubyte<1>(mk), f2 = cvt_ubyte<2>(mk), f3 = cvt_ubyte<3>(mk);
+#pragma unroll
+                        for (int r = 0; r < RH; ++r) {
+                            acc[j][r] = __builtin_fmaf(f0, pv[0][r], acc[j][r]);
+                            acc[j][r] = __builtin_fmaf(f1, pv[1][r], acc[j][r]);
+                            acc[j][r] = __builtin_fmaf(f2, pv[2][r], acc[j][r]);
+                            acc[j][r] = __builtin_fmaf(f3, pv[3][r], acc[j][r]);
+                        }
+                    }
+                }
+                w4 = w4n;
+            }
+            // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
+#pragma unroll
+            for (int j = 0; j < CPB; ++j)
+#pragma unroll
+                for (int r = 0; r < RH; ++r) {
+                    float v = acc[j][r] * __uint_as_float((uint32_t)(127 - BITS * j) << 23);
+#pragma unroll
+                    for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
+                    acc[j][r] = v;
+                }
+            if constexpr (!kSplit) __syncthreads();   // o_lds shares the region with ps: everyone is done with ps
+            if (lane < 16 * BITS) {
+#pragma unroll
+                for (int j = 0; j < CPB; ++j)
+#pragma unroll
+                    for (int r = 0; r < RH; ++r) o_lds[((size_t)wave * NR + r0 + r) * kD + Lc * CPB + j] = acc[j][r];
+            }
         }
         __syncthreads();
         for (int e = tid; e < NR * kD; e += kThreads) {
             const int r = e / kD, c = e % kD;
             float v = 0.0f;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) v += o_lds[((size_t)w * NR + r) * kD + c];
-            float zt = 0.0f;
-#pragma unroll
-            for (int rr = 0; rr < NR; ++rr)
-#pragma unroll
-                for (int m = 0; m < M; ++m)
-                    if (rr == r && m == c / GROUP) zt = zsum[rr][m];
-            po[e] = v + zt;
+            for (int w = 0; w < kWaves; ++w) v += o_lds[((size_t)w * NR + r) * kD + c] + red_z[(w * NR + r) * M + c / GROUP];
+            po[e] = v;
         }
     } else {
         // ------------------------------------------------------------ 16-bit candidates
