@@ -254,8 +254,13 @@ hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key
     const int per_lane_256 = (Nq + 255) / 256, per_lane = (Nq + 1023) / 1024;   // keys per lane held in registers
 #define SPC_TOPK(T, K) hipLaunchKernelGGL((topk_kernel<T, K>), dim3(rows), dim3(T), 0, stream, Nq, k, keys, key_stride, idx_out)
     if (per_lane_256 <= 8) SPC_TOPK(256, 8);
+    else if (per_lane_256 <= 16) SPC_TOPK(256, 16);
     else if (per_lane_256 <= 32) SPC_TOPK(256, 32);
+    else if (per_lane <= 16) SPC_TOPK(1024, 16);
+    else if (per_lane <= 24) SPC_TOPK(1024, 24);
     else if (per_lane <= 32) SPC_TOPK(1024, 32);
+    else if (per_lane <= 40) SPC_TOPK(1024, 40);
+    else if (per_lane <= 48) SPC_TOPK(1024, 48);
     else if (per_lane <= 64) SPC_TOPK(1024, 64);
     else SPC_TOPK(1024, 0);
 #undef SPC_TOPK
