@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
+    ap.add_argument("--variant", default="speculative", choices=["speculative", "nonspec"],
+                    help="nonspec: the non-speculative fetching of Section 4.4 (select on the current token, one query "
+                         "row, gather on the main stream before attend): the whole link time is exposed")
     ap.add_argument("--compute-only-pass", action="store_true",
                     help="add two more passes of K steps that issue no gathers (attend keeps reading the pairs staged "
                          "by the last gather): wall time -> compute_us_layer, event timing -> kernel_us_no_gather")
@@ -96,6 +99,7 @@ def main():
 
     nq_pool = 8
     q_all = synth.make_queries_device(seed, nq_pool * layers, B, Hq, D, dtype).view(nq_pool, layers, B, Hq, 2, D)
+    q1_all = q_all[:, :, :, :, :1].contiguous()   # current-token rows only (non-speculative variant)
     step_k, step_v = synth.make_kv_device(seed + 1, total_steps * B, Hkv, 1, D, dtype)
     step_k = step_k.view(total_steps, B, Hkv, 1, D).contiguous()
     step_v = step_v.view(total_steps, B, Hkv, 1, D).contiguous()
@@ -104,7 +108,19 @@ def main():
     out = [torch.empty((B, Hq, 2, D), dtype=torch.float32, device="cuda") for _ in range(layers)]
     state = {"t": 0}
 
+    def step_nonspec():
+        t = state["t"]
+        for L in range(layers):
+            q = q1_all[t % nq_pool, L]
+            sc.quantize_append(L, step_k[t], step_v[t], 1, main_s)
+            sc.score_topk(L, q, 1, idx[L][0], main_s)
+            sc.gather(L, idx[L][0], 0, main_s)
+            sc.attend(L, q, 1, None, None, 0, out[L], main_s)
+        state["t"] = t + 1
+
     def step(gather=True):
+        if args.variant == "nonspec":
+            return step_nonspec()
         t = state["t"]
         for L in range(layers):
             q = q_all[t % nq_pool, L]
@@ -187,7 +203,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
-                   "residual": R, "gather": not args.no_gather,
+                   "residual": R, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
                                    "main stream, gather of the next step's pairs on a side stream"},
         "score_topk_attend_us": breakdown["score_topk_attend"],
@@ -201,7 +217,7 @@ def main():
         "roofline": roofline,
     }
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.variant == "speculative":
         result["cpu_baseline"] = cpu_baseline(sc, synth, sample, k_hist, v_hist, step_k, step_v, q_all, spec_k, spec_v,
                                               state["t"], layers, B, Hq, Hkv, G, D, dtype, bits, g, R, k, nq_pool)
     print(json.dumps(result))

@@ -173,3 +173,30 @@ class Case:
         self.prev_idx = idx_h
         self.step_no += 1
         return idx_h, out_h
+
+
+    def nonspec_step(self):
+        """Non-speculative fetching (the ablation of Section 4.4 / Table 4): select on the current token's own
+        low-bit scores, fetch those pairs at once, then attend with them.  One query row, serial gather."""
+        t = self.step_no
+        q_bits = synth.make_queries(self.seed, self.B, self.Hq, self.D, self.dtype, n_rows=1, sub=t)
+        q = to_dev(q_bits, self.dtype)
+        idx = self.idx[t % 2]
+        main = torch.cuda.current_stream()
+        self.sc.score_topk(0, q, 1, idx, main)
+        self.sc.gather(0, idx, 0, main)
+        out = torch.empty((self.B, self.Hq, 1, self.D), dtype=torch.float32, device="cuda")
+        self.sc.attend(0, q, 1, None, None, 0, out, main)
+        torch.cuda.synchronize()
+        idx_h, out_h = idx.cpu().numpy(), out.cpu().numpy()
+        for (b, h) in self.sample:
+            c = self.oc[(b, h)]
+            qh = q_bits[b, h * self.G:(h + 1) * self.G]
+            _, sigma = c.scores(qh, self.sm_scale)
+            self.stats["band_diffs"] += check_topk(sigma, idx_h[b, h], self.k, what=f"non-spec top-k {(b, h)}")
+            ref_out = c.attend(qh, self.sm_scale, P=idx_h[b, h])
+            e = check_out(out_h[b, h * self.G:(h + 1) * self.G], ref_out, what=f"non-spec attend {(b, h)}")
+            self.stats["max_out_err"] = max(self.stats["max_out_err"], e)
+        self.prev_idx = idx_h
+        self.step_no += 1
+        return idx_h, out_h

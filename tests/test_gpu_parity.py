@@ -69,6 +69,20 @@ def test_pre_decoding_single_row():
         c.close()
 
 
+def test_non_speculative_fetching():
+    """Section 4.4 / Table 4 ablation: top-k from the current token, fetched before its own attention."""
+    from tests.harness import Case
+    for (Hq, Hkv, bits, g) in ((2, 2, 2, 32), (8, 2, 1, 32)):
+        c = Case(1, Hq, Hkv, 1000, synth.FP16, bits, g, 48, seed=2250, n_rows=1)
+        try:
+            c.load()
+            for t in range(2):
+                c.append_token(t)
+                c.nonspec_step()
+        finally:
+            c.close()
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
