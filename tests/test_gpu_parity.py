@@ -51,6 +51,36 @@ def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
     print(stats)
 
 
+@pytest.mark.parametrize("dtype,bits,g", [(synth.FP16, 2, 32), (synth.BF16, 2, 64), (synth.FP16, 1, 32), (synth.BF16, 1, 64)])
+def test_quantiser_on_rounding_boundaries(dtype, bits, g):
+    """Inputs on a grid of half quantisation steps (and their 16-bit neighbours), constant groups and groups
+    with tiny ranges: the quotients of Eq. 2 / Eq. 3 land exactly on, or one rounding away from, the
+    round-half-up boundaries, where codes have to stay bit-exact."""
+    from tests.harness import Case
+    c = Case(1, 2, 2, 1024, dtype, bits, g, 16, seed=4242)
+    rng = np.random.default_rng(77)
+    shape = c.k_bits.shape
+    for name in ("k_bits", "v_bits"):
+        m = rng.integers(0, 7 if bits == 2 else 5, size=shape)              # half steps of a unit-scale group
+        e = rng.integers(-6, 5, size=(shape[0], shape[1], shape[2] // g, 1)).repeat(g, axis=2)
+        if name == "v_bits":
+            e = rng.integers(-6, 5, size=(shape[0], shape[1], shape[2], shape[3] // g)).repeat(g, axis=3)
+        x = (m * 0.5) * np.exp2(e.astype(np.float64)) - (1.0 if bits == 1 else 0.0)
+        b = synth.to_bits(x.astype(np.float32), dtype).astype(np.int32)
+        b = b + rng.integers(-1, 2, size=shape) * (rng.random(shape) < 0.3)  # neighbours in the 16-bit format
+        b[:, :, 64:96] = b[:, :, 64:65]                                       # constant key groups: s = 0
+        b[:, :, 200:210, :] = b[:, :, 200:210, :1]                            # constant value groups
+        b = np.where((b & 0x7FFF) >= (0x7C00 if dtype == synth.FP16 else 0x7F80), 0, b)   # no inf / nan
+        setattr(c, name, b.astype(np.uint16))
+    try:
+        c.load()
+        c.check_quantized()
+        c.append_token(0)
+        c.decode_step()
+    finally:
+        c.close()
+
+
 def test_streamed_load_equals_bulk_load():
     """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
     from tests.harness import Case
