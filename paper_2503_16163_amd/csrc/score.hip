@@ -7,15 +7,18 @@
 // qs[r][c] and the constant qz[r] are shared by the tokens of a group.
 //
 // Mapping: one workgroup of four waves per 512-token tile, each wave taking a quarter of
-// the channels (code dwords) and wave 0 adding up the partial sums.  A lane scores 8 consecutive tokens of one
-// 32-token sub-group; the four lanes of a quad cover that sub-group and together hold
-// its 128 multipliers per query row in "quad layout" (quad lane k holds channel
-// 4v + k in register v), computed by the quad itself straight from the metadata.
-// Per multiplier register v the value of channel 4v + b is broadcast inside the quad with
-// one DPP move and then feeds eight plain (full-rate) multiply-accumulates, one per
-// token; codes become floats with v_cvt_f32_ubyte{0..3} after one mask per four codes.
-// (Measured on MI355X: v_fmac_f32 issues at twice the rate of its DPP form, of the
-// conversions and of integer ops, so the broadcast is paid once per 8 tokens.)
+// the channels (code dwords) and wave 0 adding up the partial sums.  A lane scores 8
+// consecutive tokens of one 32-token sub-group; the four lanes of a quad cover that
+// sub-group and fold its multipliers straight from the metadata, quad lane k those of the
+// channels with channel % 4 == k.  With one or two query rows the quad exchanges them through
+// LDS (a wave-private area: one 8-byte write and two 16-byte reads per mask) so that they
+// reach the multiply-accumulates as plain register operands; with more rows they stay in
+// registers and are broadcast inside the quad with DPP moves, one per 8 tokens.  Codes
+// become floats with v_cvt_f32_ubyte{0..3} after one mask per four codes.
+// Measured on MI355X, with every load of the kernel served from cache: the kernel takes as
+// long as with the loads from HBM less about a tenth, and its time follows the count of
+// vector instructions (two multiply-accumulates and one conversion per code) at four clocks
+// each; a DPP move costs more than twice that, which is why the LDS exchange pays.
 #include "kernels.h"
 #include "layout.h"
 
@@ -58,7 +61,12 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
     // query rows in quad layout [row][channel % 4][channel / 4], rows of 32 padded to 36 floats so
     // that the four quad lanes read different banks
     __shared__ __attribute__((aligned(16))) float qfq[NR][4][36];
-    __shared__ float part[kScoreWaves - 1][NP][64];
+    // Per wave: first the multipliers it folds, [sub-group][mask][channel % 4][row] with the
+    // sub-groups 8 floats apart in bank space; once it has scored its share, its partial sums.
+    constexpr bool kLdsMult = NR <= 2;
+    constexpr int kMultQuad = WPW * HPD * 4 * NR + 8;
+    constexpr int kWaveFloats = (kLdsMult && 16 * kMultQuad > NP * 64) ? 16 * kMultQuad : NP * 64;
+    __shared__ __attribute__((aligned(16))) float wsm[kScoreWaves][kWaveFloats];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, k = lane & 3;
     const int row = blockIdx.y, tile = blockIdx.x;
@@ -97,6 +105,71 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
 #pragma unroll
         for (int r = 0; r < NR; ++r) acc[s][r] = 0.0f;
 
+    if constexpr (kLdsMult) {
+        // Every lane folds the multipliers of its channel class (channel % 4 == k) for all masks of
+        // this wave and leaves them in LDS, from where the four lanes of the quad read all four
+        // classes back as plain operands: the lanes of a wave run in lockstep and LDS serves one
+        // wave's accesses in order, so no workgroup barrier is involved.
+        float* mq = &wsm[wave][(lane >> 2) * kMultQuad];
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+            const int W = wave * WPW + i;
+#pragma unroll
+            for (int h = 0; h < HPD; ++h) {
+                const uint32_t m = comp(mt[i][h / 4], h % 4);
+                float sc, z;
+                derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), sc, z);
+                const float sf = sc * __uint_as_float((uint32_t)(127 - BITS * h) << 23);
+                float qs[NR];
+#pragma unroll
+                for (int r = 0; r < NR; ++r) {
+                    const float qv = qfq[r][k][HPD * W + h];
+                    qs[r] = qv * sf;
+                    qz[r] = __builtin_fmaf(qv, z, qz[r]);
+                }
+                float* dst = mq + ((i * HPD + h) * 4 + k) * NR;
+                if constexpr (NR == 2) *reinterpret_cast<float2*>(dst) = make_float2(qs[0], qs[1]);
+                else dst[0] = qs[0];
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int i = 0; i < WPW; ++i) {
+#pragma unroll
+            for (int h = 0; h < HPD; ++h) {
+                float b[4][NR];
+                const float* src = mq + (i * HPD + h) * 4 * NR;
+                if constexpr (NR == 2) {
+                    const float4 t0 = *reinterpret_cast<const float4*>(src), t1 = *reinterpret_cast<const float4*>(src + 4);
+                    b[0][0] = t0.x; b[0][1] = t0.y; b[1][0] = t0.z; b[1][1] = t0.w;
+                    b[2][0] = t1.x; b[2][1] = t1.y; b[3][0] = t1.z; b[3][1] = t1.w;
+                } else {
+                    const float4 t0 = *reinterpret_cast<const float4*>(src);
+                    b[0][0] = t0.x; b[1][0] = t0.y; b[2][0] = t0.z; b[3][0] = t0.w;
+                }
+                float f[kTok][4];
+#pragma unroll
+                for (int s = 0; s < kTok; ++s) {
+                    const uint32_t mk = comp(cw[i][s / 4], s % 4) & (MASK << (BITS * h));
+                    f[s][0] = cvt_ubyte<0>(mk);
+                    f[s][1] = cvt_ubyte<1>(mk);
+                    f[s][2] = cvt_ubyte<2>(mk);
+                    f[s][3] = cvt_ubyte<3>(mk);
+                }
+#pragma unroll
+                for (int r = 0; r < NR; ++r)
+#pragma unroll
+                    for (int s = 0; s < kTok; ++s) {
+                        acc[s][r] = __builtin_fmaf(f[s][0], b[0][r], acc[s][r]);
+                        acc[s][r] = __builtin_fmaf(f[s][1], b[1][r], acc[s][r]);
+                        acc[s][r] = __builtin_fmaf(f[s][2], b[2][r], acc[s][r]);
+                        acc[s][r] = __builtin_fmaf(f[s][3], b[3][r], acc[s][r]);
+                    }
+            }
+        }
+    } else {
 #pragma unroll
     for (int i = 0; i < WPW; ++i) {
         const int W = wave * WPW + i;
@@ -146,25 +219,27 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
         }
     }
 
+    }
+
     // waves 1.. hand their partial sums to wave 0
     if (wave > 0) {
 #pragma unroll
         for (int s = 0; s < kTok; ++s)
 #pragma unroll
-            for (int r = 0; r < NR; ++r) part[wave - 1][s * NR + r][lane] = acc[s][r];
+            for (int r = 0; r < NR; ++r) wsm[wave][(s * NR + r) * 64 + lane] = acc[s][r];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) part[wave - 1][kTok * NR + r][lane] = qz[r];
+        for (int r = 0; r < NR; ++r) wsm[wave][(kTok * NR + r) * 64 + lane] = qz[r];
     }
     __syncthreads();
     if (wave > 0) return;
 #pragma unroll
-    for (int w = 0; w < kScoreWaves - 1; ++w) {
+    for (int w = 1; w < kScoreWaves; ++w) {
 #pragma unroll
         for (int s = 0; s < kTok; ++s)
 #pragma unroll
-            for (int r = 0; r < NR; ++r) acc[s][r] += part[w][s * NR + r][lane];
+            for (int r = 0; r < NR; ++r) acc[s][r] += wsm[w][(s * NR + r) * 64 + lane];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) qz[r] += part[w][kTok * NR + r][lane];
+        for (int r = 0; r < NR; ++r) qz[r] += wsm[w][(kTok * NR + r) * 64 + lane];
     }
     // the zero-point term: sum over the quad's four channel classes
 #pragma unroll
