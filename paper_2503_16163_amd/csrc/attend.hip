@@ -246,7 +246,16 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             m_row[r] = v;
         }
 
-        // p = exp(l - m); p * s per (token, value group); the zero-point term; the row sums
+        // p = exp(l - m); p * s per (token, value group); the zero-point term sum_i p_i z[i][m] and
+        // the row sums sum_i p_i.  With up to four query rows every thread adds up its own tokens
+        // and the waves reduce those sums.  With more rows a thread has one token and NR * (M + 1)
+        // sums, too many wave reductions: p and z go to LDS instead (in the area the merged
+        // outputs use later) and the lanes re-read them as (row, slice of this wave's tokens), so
+        // that only the slices of a row are left to add up.
+        constexpr int kPl = NR + 1;              // row pitch of the p plane: lanes of one read in distinct banks
+        float* pl = o_lds;                       // [CH][kPl]
+        float* zl = o_lds + CH * kPl;            // [CH][M]
+        static_assert(!kSplit || CH * kPl + CH * M <= kOl, "p and z planes must fit the merged-output area");
         float zacc[NR][M], sloc[NR];
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
@@ -263,28 +272,65 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 for (int r = 0; r < NR; ++r) {
                     const float ms = m_row[r] == -INFINITY ? 0.0f : m_row[r];
                     p[r] = __expf(lgr[tt][r] - ms);
-                    sloc[r] += p[r];
+                    if constexpr (kSplit) pl[i * kPl + r] = p[r];
+                    else sloc[r] += p[r];
                 }
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     float sc, z;
                     derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
+                    if constexpr (kSplit) zl[i * M + m] = z;
 #pragma unroll
                     for (int r = 0; r < NR; ++r) {
                         ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
-                        zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                        if constexpr (!kSplit) zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
                     }
                 }
             }
         }
+        if constexpr (kSplit) {
+            __syncthreads();
+            constexpr int S = 64 / NR;                    // slices per row inside a wave
+            constexpr int T = (CH / kWaves) / S;          // tokens per lane
+            static_assert(S == 8 || S == 4, "slice reduction below covers 4 or 8 adjacent lanes");
+            const int r = lane / S, slice = lane % S;
+            float sa = 0.0f, za[M];
 #pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            const float v = wave_sum(sloc[r]);
-            if (lane == 0) red_sum[wave * NR + r] = v;
+            for (int m = 0; m < M; ++m) za[m] = 0.0f;
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                const int i = wave * (CH / kWaves) + slice * T + j;
+                if (i < n) {
+                    const float pr = pl[i * kPl + r];
+                    sa += pr;
+#pragma unroll
+                    for (int m = 0; m < M; ++m) za[m] = __builtin_fmaf(pr, zl[i * M + m], za[m]);
+                }
+            }
+            sa += dpp_move<kDppXor1>(sa);
+            sa += dpp_move<kDppXor2>(sa);
+            if constexpr (S == 8) sa += dpp_move<kDppHalfMirror>(sa);
 #pragma unroll
             for (int m = 0; m < M; ++m) {
-                const float zv = wave_sum(zacc[r][m]);
-                if (lane == 0) red_z[(wave * NR + r) * M + m] = zv;
+                za[m] += dpp_move<kDppXor1>(za[m]);
+                za[m] += dpp_move<kDppXor2>(za[m]);
+                if constexpr (S == 8) za[m] += dpp_move<kDppHalfMirror>(za[m]);
+            }
+            if (slice == 0) {
+                red_sum[wave * NR + r] = sa;
+#pragma unroll
+                for (int m = 0; m < M; ++m) red_z[(wave * NR + r) * M + m] = za[m];
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const float v = wave_sum(sloc[r]);
+                if (lane == 0) red_sum[wave * NR + r] = v;
+#pragma unroll
+                for (int m = 0; m < M; ++m) {
+                    const float zv = wave_sum(zacc[r][m]);
+                    if (lane == 0) red_z[(wave * NR + r) * M + m] = zv;
+                }
             }
         }
         __syncthreads();
@@ -498,24 +544,26 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 }
 
 // Merge the chunk partials of one (KV head, query row): o = sum_c o_c e^(m_c - m) / sum_c l_c e^(m_c - m).
-// 256 threads = 4 slices of the chunk list x 64 channel pairs; the chunk weights are
+// 1024 threads = 16 slices of the chunk list x 64 channel pairs; the chunk weights are
 // computed once into LDS so that the partial-output loads are independent of each other.
 // (Folding this into the partial kernel behind a "last workgroup" counter needs a
 // device-scope fence in every workgroup, which writes back and invalidates the L2 of
 // its XCD; measured, that made the kernel eight times slower than this extra launch.)
 constexpr int kCombineMaxChunks = 1280;
-__global__ __launch_bounds__(256) void attend_combine_kernel(const float* __restrict__ part_o,
-                                                             const float* __restrict__ part_ml, int max_chunks,
-                                                             int n_chunks, int NR, float* __restrict__ out) {
+constexpr int kCombineThreads = 1024, kCombineSlices = kCombineThreads / 64;
+__global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const float* __restrict__ part_o,
+                                                                         const float* __restrict__ part_ml,
+                                                                         int max_chunks, int n_chunks, int NR,
+                                                                         float* __restrict__ out) {
     __shared__ float wgt[kCombineMaxChunks];
-    __shared__ float red[8];
-    __shared__ float2 osum[4][64];
+    __shared__ float red[2 * kCombineSlices];
+    __shared__ float2 osum[kCombineSlices][64];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int row = blockIdx.x / NR, r = blockIdx.x % NR;
     const float* ml = part_ml + ((size_t)row * max_chunks * NR + r) * 2;
     const size_t ml_stride = (size_t)NR * 2;
     float mloc = -INFINITY;
-    for (int ch = tid; ch < n_chunks; ch += 256) {
+    for (int ch = tid; ch < n_chunks; ch += kCombineThreads) {
         const float m = ml[ch * ml_stride];
         wgt[ch] = m;
         mloc = fmaxf(mloc, m);
@@ -523,32 +571,36 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* __rest
     mloc = wave_max(mloc);
     if (lane == 0) red[wave] = mloc;
     __syncthreads();
-    const float mmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float mmax = red[0];
+#pragma unroll
+    for (int w = 1; w < kCombineSlices; ++w) mmax = fmaxf(mmax, red[w]);
     float dloc = 0.0f;
-    for (int ch = tid; ch < n_chunks; ch += 256) {
+    for (int ch = tid; ch < n_chunks; ch += kCombineThreads) {
         const float m = wgt[ch];
         const float w = m == -INFINITY ? 0.0f : __expf(m - mmax);
         wgt[ch] = w;
         dloc = __builtin_fmaf(ml[ch * ml_stride + 1], w, dloc);
     }
     dloc = wave_sum(dloc);
-    if (lane == 0) red[4 + wave] = dloc;
+    if (lane == 0) red[kCombineSlices + wave] = dloc;
     __syncthreads();
-    const float den = red[4] + red[5] + red[6] + red[7];
-    const int cp = tid % 64, slice = tid / 64;
+    float den = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kCombineSlices; ++w) den += red[kCombineSlices + w];
+    const int cp = lane, slice = wave;
     const float2* po = reinterpret_cast<const float2*>(part_o + ((size_t)row * max_chunks * NR + r) * kD) + cp;
     const size_t po_stride = (size_t)NR * kD / 2;
     float2 o = make_float2(0.f, 0.f);
-    for (int c0 = slice; c0 < n_chunks; c0 += 4 * 8) {
+    for (int c0 = slice; c0 < n_chunks; c0 += kCombineSlices * 8) {
         float2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int ch = c0 + 4 * u;
+            const int ch = c0 + kCombineSlices * u;
             v[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int ch = c0 + 4 * u;
+            const int ch = c0 + kCombineSlices * u;
             const float w = ch < n_chunks ? wgt[ch] : 0.0f;
             if (w != 0.0f) {   // a chunk without candidates may hold anything
                 o.x = __builtin_fmaf(v[u].x, w, o.x);
@@ -559,10 +611,14 @@ __global__ __launch_bounds__(256) void attend_combine_kernel(const float* __rest
     osum[slice][cp] = o;
     __syncthreads();
     if (tid < 64) {
-        const float2 a = osum[0][tid], b = osum[1][tid], c = osum[2][tid], d = osum[3][tid];
-        float2 res;
-        res.x = (a.x + b.x + c.x + d.x) / den;
-        res.y = (a.y + b.y + c.y + d.y) / den;
+        float2 res = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int w = 0; w < kCombineSlices; ++w) {
+            res.x += osum[w][tid].x;
+            res.y += osum[w][tid].y;
+        }
+        res.x /= den;
+        res.y /= den;
         reinterpret_cast<float2*>(out + ((size_t)row * NR + r) * kD)[tid] = res;
     }
 }
@@ -578,7 +634,7 @@ hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* 
         hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, 0, stream, L, A);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(256), 0, stream, A.part_o, A.part_ml,
+    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(kCombineThreads), 0, stream, A.part_o, A.part_ml,
                        A.max_chunks, A.n_main + n_extra, NR, out);
     return hipGetLastError();
 }

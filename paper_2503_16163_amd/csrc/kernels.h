@@ -34,9 +34,16 @@ hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void*
 hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
 
-// top-k over keys[row][0..Nq): idx_out [rows][k], ascending, -1 padded
+// top-k over keys[row][0..Nq): idx_out [rows][k], ascending, -1 padded.  Rows too long for one
+// workgroup's registers are selected in two launches through the candidate buffers.
+struct TopkScratch {
+    uint32_t* cand_keys;   // [rows][max_parts][k]
+    int32_t* cand_idx;     // [rows][max_parts][k]
+    int max_parts;
+};
+int topk_parts(int Nq, int k);   // ranges a row of Nq keys is split into (1 = single launch)
 hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
-                       hipStream_t stream);
+                       const TopkScratch& scratch, hipStream_t stream);
 
 // gather rows idx[row][j] of the host store into slot [rows][k][256] and slot_idx [rows][k]
 hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,

@@ -47,6 +47,7 @@ struct specache_ctx {
     uint32_t* keys = nullptr;    // [rows][logit_stride]
     size_t logit_stride = 0;
     AttendScratch scratch{};
+    TopkScratch topk_scratch{};
     int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
     std::string err;
     // optional per-kernel timing: (start, stop) event pairs recorded around each launch
@@ -130,6 +131,8 @@ void free_all(specache_ctx* ctx) {
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->scratch.part_o);
     (void)hipFree(ctx->scratch.part_ml);
+    (void)hipFree(ctx->topk_scratch.cand_keys);
+    (void)hipFree(ctx->topk_scratch.cand_idx);
 }
 
 }  // namespace
@@ -225,6 +228,12 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     ctx->scratch.max_chunks = max_main + (c.topk + c.residual + 1 + ec - 1) / ec;
     SPC_ALLOC(hipMalloc((void**)&ctx->scratch.part_o, (size_t)rows * ctx->scratch.max_chunks * G * 2 * kD * 4));
     SPC_ALLOC(hipMalloc((void**)&ctx->scratch.part_ml, (size_t)rows * ctx->scratch.max_chunks * G * 2 * 2 * 4));
+    ctx->topk_scratch.max_parts = topk_parts((int)cap, c.topk);
+    if (ctx->topk_scratch.max_parts > 1) {
+        const size_t n = (size_t)rows * ctx->topk_scratch.max_parts * c.topk;
+        SPC_ALLOC(hipMalloc((void**)&ctx->topk_scratch.cand_keys, n * 4));
+        SPC_ALLOC(hipMalloc((void**)&ctx->topk_scratch.cand_idx, n * 4));
+    }
     SPC_ALLOC(hipDeviceSynchronize());
 #undef SPC_ALLOC
     *out = ctx;
@@ -291,7 +300,8 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     }
     {
         TimedLaunch t(ctx, st, SPECACHE_K_TOPK);
-        SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out, st));
+        SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out,
+                                 ctx->topk_scratch, st));
     }
     SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;

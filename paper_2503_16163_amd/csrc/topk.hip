@@ -72,10 +72,21 @@ __device__ __forceinline__ void select_bin_wave0(const uint32_t* hist, uint32_t*
     if (found_bin != 0xFFFFFFFFu) { sel[0] = found_bin; sel[1] = found_rank; }
 }
 
+// A row may be split into `parts` ranges of part_len keys, one workgroup each, that write
+// their selections (position in the row, and the key if key_out is set) side by side; a
+// second launch then selects among those candidates and translates its positions through
+// `map`.  parts == 1, map == key_out == null is the plain single-launch selection.
+struct TopkIo {
+    int nq_total, parts, part_len;
+    const int32_t* map;      // [rows][map_stride] or null
+    size_t map_stride;
+    uint32_t* key_out;       // [rows * parts][k] or null
+};
+
 // THREADS: 1024 for long rows; 256 for rows of up to 8192 keys, so that several rows share a
 // compute unit and hide each other's barrier latency.
 template <int THREADS, int KPT>
-__global__ __launch_bounds__(THREADS) void topk_kernel(int Nq, int k, const uint32_t* __restrict__ keys,
+__global__ __launch_bounds__(THREADS) void topk_kernel(TopkIo io, int k, const uint32_t* __restrict__ keys,
                                                        size_t key_stride, int32_t* __restrict__ idx_out) {
     constexpr int kTopkThreads = THREADS;
     constexpr int kTopkWaves = THREADS / 64;
@@ -87,15 +98,29 @@ __global__ __launch_bounds__(THREADS) void topk_kernel(int Nq, int k, const uint
     __shared__ uint32_t result[2];     // tau, number of keys == tau to take
     __shared__ uint32_t wave_gt[kTopkWaves], wave_eq[kTopkWaves];
 
-    const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const uint32_t* kr = keys + (size_t)row * key_stride;
-    int32_t* out = idx_out + (size_t)row * k;
+    const int row = blockIdx.x / io.parts, part = blockIdx.x % io.parts;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int base = part * io.part_len;
+    const int left = io.nq_total - base;
+    const int Nq = left < 0 ? 0 : (left < io.part_len ? left : io.part_len);   // keys of this range
+    const uint32_t* kr = keys + (size_t)row * key_stride + base;
+    int32_t* out = idx_out + (size_t)blockIdx.x * k;
+    uint32_t* kout = io.key_out ? io.key_out + (size_t)blockIdx.x * k : nullptr;
+    const int32_t* map = io.map ? io.map + (size_t)row * io.map_stride : nullptr;
     const int keff = k < Nq ? k : Nq;
+    // output slot `pos` receives local position i, whose key is kv
+    auto emit = [&](uint32_t pos, int i, uint32_t kv) {
+        out[pos] = map ? map[i] : base + i;
+        if (kout) kout[pos] = kv;
+    };
 
-    for (int j = keff + tid; j < k; j += kTopkThreads) out[j] = -1;
+    for (int j = keff + tid; j < k; j += kTopkThreads) {
+        out[j] = -1;
+        if (kout) kout[j] = 0u;     // below every key: never selected by the second launch
+    }
     if (keff == 0) return;
     if (keff == Nq) {   // everything is selected
-        for (int j = tid; j < Nq; j += kTopkThreads) out[j] = j;
+        for (int j = tid; j < Nq; j += kTopkThreads) emit(j, j, kr[j]);
         return;
     }
 
@@ -240,22 +265,24 @@ __global__ __launch_bounds__(THREADS) void topk_kernel(int Nq, int k, const uint
         const uint32_t my_eq_rank = eq_before + prefix_below(me);
         if (gt || (eq && my_eq_rank < need)) {
             const uint32_t eq_taken_before = my_eq_rank < need ? my_eq_rank : need;
-            out[gt_before + prefix_below(mg) + eq_taken_before] = i;
+            emit(gt_before + prefix_below(mg) + eq_taken_before, i, kv);
         }
         gt_before += __popcll(mg);
         eq_before += __popcll(me);
     });
 }
 
-}  // namespace
-
-hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
-                       hipStream_t stream) {
-    const int per_lane_256 = (Nq + 255) / 256, per_lane = (Nq + 1023) / 1024;   // keys per lane held in registers
-#define SPC_TOPK(T, K) hipLaunchKernelGGL((topk_kernel<T, K>), dim3(rows), dim3(T), 0, stream, Nq, k, keys, key_stride, idx_out)
-    if (per_lane_256 <= 8) SPC_TOPK(256, 8);
-    else if (per_lane_256 <= 16) SPC_TOPK(256, 16);
-    else if (per_lane_256 <= 32) SPC_TOPK(256, 32);
+// one launch over `rows * io.parts` ranges of at most n keys each
+hipError_t launch_ranges(int rows, int n, const TopkIo& io, int k, const uint32_t* keys, size_t key_stride,
+                         int32_t* idx_out, hipStream_t stream) {
+    const int per_lane_256 = (n + 255) / 256, per_lane = (n + 1023) / 1024;   // keys per lane held in registers
+#define SPC_TOPK(T, K) \
+    hipLaunchKernelGGL((topk_kernel<T, K>), dim3(rows * io.parts), dim3(T), 0, stream, io, k, keys, key_stride, idx_out)
+    // the floor of step 1 needs more threads than k to bite: small workgroups only for small k
+    const bool small_wg = k <= 256;
+    if (small_wg && per_lane_256 <= 8) SPC_TOPK(256, 8);
+    else if (small_wg && per_lane_256 <= 16) SPC_TOPK(256, 16);
+    else if (small_wg && per_lane_256 <= 32) SPC_TOPK(256, 32);
     else if (per_lane <= 16) SPC_TOPK(1024, 16);
     else if (per_lane <= 24) SPC_TOPK(1024, 24);
     else if (per_lane <= 32) SPC_TOPK(1024, 32);
@@ -265,6 +292,36 @@ hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key
     else SPC_TOPK(1024, 0);
 #undef SPC_TOPK
     return hipGetLastError();
+}
+
+}  // namespace
+
+// Rows longer than the registers of one workgroup hold (65536 keys) are split into ranges of
+// about kTopkPartKeys keys, as many as keep the candidate list of the second launch within
+// one workgroup's registers.
+constexpr int kTopkRegisterKeys = 65536, kTopkPartKeys = 16384;
+
+int topk_parts(int Nq, int k) {
+    if (Nq <= kTopkRegisterKeys || k <= 0) return 1;
+    int parts = (Nq + kTopkPartKeys - 1) / kTopkPartKeys;
+    const int most = kTopkRegisterKeys / k;
+    parts = parts < most ? parts : most;
+    return parts < 2 ? 1 : parts;
+}
+
+hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
+                       const TopkScratch& scratch, hipStream_t stream) {
+    const int parts = topk_parts(Nq, k);
+    if (parts > 1 && parts <= scratch.max_parts && scratch.cand_keys && scratch.cand_idx) {
+        const int part_len = (((Nq + parts - 1) / parts) + 63) / 64 * 64;
+        TopkIo first{Nq, parts, part_len, nullptr, 0, scratch.cand_keys};
+        hipError_t e = launch_ranges(rows, part_len, first, k, keys, key_stride, scratch.cand_idx, stream);
+        if (e != hipSuccess) return e;
+        TopkIo second{parts * k, 1, parts * k, scratch.cand_idx, (size_t)parts * k, nullptr};
+        return launch_ranges(rows, parts * k, second, k, scratch.cand_keys, (size_t)parts * k, idx_out, stream);
+    }
+    TopkIo io{Nq, 1, Nq, nullptr, 0, nullptr};
+    return launch_ranges(rows, Nq, io, k, keys, key_stride, idx_out, stream);
 }
 
 }  // namespace specache

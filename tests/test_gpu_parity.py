@@ -81,6 +81,25 @@ def test_quantiser_on_rounding_boundaries(dtype, bits, g):
         c.close()
 
 
+def test_long_row_topk_in_two_launches_keeps_the_tie_rule():
+    """A row longer than one workgroup's registers (> 65536 keys) is selected in two launches.  Keys repeat with
+    period 32, so every group quantises alike and the scores form 32 classes of exactly equal values: the k-th
+    boundary falls inside a class and ArgTopK has to keep that class's lowest positions, across the ranges."""
+    from tests.harness import Case
+    S, k = 70000, 3000
+    c = Case(1, 1, 1, S, synth.FP16, 2, 32, k, seed=555, n_rows=2)
+    c.k_bits = np.ascontiguousarray(c.k_bits[:, :, np.arange(S) % 32])
+    try:
+        c.load()
+        c.append_token(0)
+        c.decode_step()
+        assert c.stats["band_diffs"] == 0, c.stats
+        _, nq = c.sc.counts(0)
+        assert nq > 65536
+    finally:
+        c.close()
+
+
 def test_streamed_load_equals_bulk_load():
     """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
     from tests.harness import Case
