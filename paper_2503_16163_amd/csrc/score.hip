@@ -7,18 +7,20 @@
 // qs[r][c] and the constant qz[r] are shared by the tokens of a group.
 //
 // Mapping: one workgroup of four waves per 512-token tile, each wave taking a quarter of
-// the channels (code dwords) and wave 0 adding up the partial sums.  A lane scores 8
-// consecutive tokens of one 32-token sub-group; the four lanes of a quad cover that
-// sub-group and fold its multipliers straight from the metadata, quad lane k those of the
-// channels with channel % 4 == k.  With one or two query rows the quad exchanges them through
-// LDS (a wave-private area: one 8-byte write and two 16-byte reads per mask) so that they
-// reach the multiply-accumulates as plain register operands; with more rows they stay in
-// registers and are broadcast inside the quad with DPP moves, one per 8 tokens.  Codes
-// become floats with v_cvt_f32_ubyte{0..3} after one mask per four codes.
+// the channels (code dwords).  A lane scores 8 consecutive tokens of one 32-token sub-group;
+// the four lanes of a quad cover that sub-group and fold its multipliers straight from the
+// metadata, quad lane k those of the channels with channel % 4 == k, and exchange them
+// through a wave-private LDS area (one vector write and up to four 16-byte reads per mask)
+// so that they reach the multiply-accumulates as plain register operands.  Codes become
+// floats with v_cvt_f32_ubyte{0..3} after one mask per four codes.  Query rows are taken in
+// passes of at most four (a pass converts the codes again, but 32 accumulators instead of up
+// to 128 keep four waves per SIMD resident); after a pass the waves swap partial sums through
+// the same LDS area and each finishes, stores and ranks two of the lane's eight tokens.
 // Measured on MI355X, with every load of the kernel served from cache: the kernel takes as
 // long as with the loads from HBM less about a tenth, and its time follows the count of
-// vector instructions (two multiply-accumulates and one conversion per code) at four clocks
-// each; a DPP move costs more than twice that, which is why the LDS exchange pays.
+// vector instructions (per code one multiply-accumulate per query row and one conversion
+// per pass) at four clocks each; a DPP move costs more than twice that, which is why the
+// multipliers travel through LDS.
 #include "kernels.h"
 #include "layout.h"
 
@@ -35,10 +37,9 @@ __device__ __forceinline__ float cvt_ubyte(uint32_t w) {
     return f;
 }
 
-// value of quad lane K's register, in every lane of the quad
-template <int K>
-__device__ __forceinline__ float quad_bcast(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x55 * K, 0xf, 0xf, true));
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
 __device__ __forceinline__ uint32_t comp(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
@@ -53,19 +54,20 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
                                                                  size_t logit_stride, uint32_t* __restrict__ keys,
                                                                  size_t key_stride) {
     constexpr int NR = G * NROWS;              // query rows sharing this KV head
+    constexpr int RH = NR < 4 ? NR : 4;        // query rows per pass
     constexpr int HPD = (32 / BITS) / 4;       // masks (= multiplier registers) per code dword
     constexpr int NW = 4 * BITS;               // code dwords per token
     constexpr int WPW = NW / kScoreWaves;      // code dwords per wave
-    constexpr int NP = kTok * NR + NR;         // partial sums per lane: logits and the zero-point terms
+    constexpr int TPW = kTok / kScoreWaves;    // tokens of a lane that one wave finishes
+    constexpr bool kRowSplit = G == 1 && NROWS == 2;
     constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
     // query rows in quad layout [row][channel % 4][channel / 4], rows of 32 padded to 36 floats so
     // that the four quad lanes read different banks
     __shared__ __attribute__((aligned(16))) float qfq[NR][4][36];
-    // Per wave: first the multipliers it folds, [sub-group][mask][channel % 4][row] with the
+    // Per wave: first the multipliers of a pass, [sub-group][mask][channel % 4][row] with the
     // sub-groups 8 floats apart in bank space; once it has scored its share, its partial sums.
-    constexpr bool kLdsMult = NR <= 2;
-    constexpr int kMultQuad = WPW * HPD * 4 * NR + 8;
-    constexpr int kWaveFloats = (kLdsMult && 16 * kMultQuad > NP * 64) ? 16 * kMultQuad : NP * 64;
+    constexpr int kMultQuad = WPW * HPD * 4 * RH + 8;
+    constexpr int kWaveFloats = 16 * kMultQuad > kTok * RH * 64 ? 16 * kMultQuad : kTok * RH * 64;
     __shared__ __attribute__((aligned(16))) float wsm[kScoreWaves][kWaveFloats];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, k = lane & 3;
@@ -96,21 +98,35 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
     }
     __syncthreads();
 
-    float acc[kTok][NR];
-    float qz[NR];
+    float* mq = &wsm[wave][(lane >> 2) * kMultQuad];
+    const int i0 = sub * kBlockTokens + kTok * k + TPW * wave;   // first of the tokens this wave finishes for the lane
+    float best[TPW];
 #pragma unroll
-    for (int r = 0; r < NR; ++r) qz[r] = 0.0f;
-#pragma unroll
-    for (int s = 0; s < kTok; ++s)
-#pragma unroll
-        for (int r = 0; r < NR; ++r) acc[s][r] = 0.0f;
+    for (int t = 0; t < TPW; ++t) best[t] = -INFINITY;
 
-    if constexpr (kLdsMult) {
-        // Every lane folds the multipliers of its channel class (channel % 4 == k) for all masks of
-        // this wave and leaves them in LDS, from where the four lanes of the quad read all four
-        // classes back as plain operands: the lanes of a wave run in lockstep and LDS serves one
-        // wave's accesses in order, so no workgroup barrier is involved.
-        float* mq = &wsm[wave][(lane >> 2) * kMultQuad];
+#pragma unroll 1
+    for (int r0 = 0; r0 < NR; r0 += RH) {
+        if constexpr (NR > RH) {
+            // Everything derived from the loaded dwords is the same in every pass; hoisting it out of
+            // the loop would cost the registers the passes are there to save, so the loads are
+            // made to look pass-dependent.
+#pragma unroll
+            for (int i = 0; i < WPW; ++i) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    asm volatile("" : "+v"(cw[i][j].x), "+v"(cw[i][j].y), "+v"(cw[i][j].z), "+v"(cw[i][j].w));
+#pragma unroll
+                for (int j = 0; j < HPD / 4; ++j)
+                    asm volatile("" : "+v"(mt[i][j].x), "+v"(mt[i][j].y), "+v"(mt[i][j].z), "+v"(mt[i][j].w));
+            }
+        }
+        // Every lane folds the multipliers of its channel class for all masks of this wave and
+        // leaves them in LDS, from where the four lanes of the quad read all four classes back:
+        // the lanes of a wave run in lockstep and LDS serves one wave's accesses in order, so
+        // no workgroup barrier is involved.
+        float qz[RH];
+#pragma unroll
+        for (int r = 0; r < RH; ++r) qz[r] = 0.0f;
 #pragma unroll
         for (int i = 0; i < WPW; ++i) {
             const int W = wave * WPW + i;
@@ -119,35 +135,42 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
                 const uint32_t m = comp(mt[i][h / 4], h % 4);
                 float sc, z;
                 derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), sc, z);
+                // the codes of mask h arrive scaled by 2^(BITS*h)
                 const float sf = sc * __uint_as_float((uint32_t)(127 - BITS * h) << 23);
-                float qs[NR];
+                float qs[RH];
 #pragma unroll
-                for (int r = 0; r < NR; ++r) {
-                    const float qv = qfq[r][k][HPD * W + h];
+                for (int r = 0; r < RH; ++r) {
+                    const float qv = qfq[r0 + r][k][HPD * W + h];
                     qs[r] = qv * sf;
                     qz[r] = __builtin_fmaf(qv, z, qz[r]);
                 }
-                float* dst = mq + ((i * HPD + h) * 4 + k) * NR;
-                if constexpr (NR == 2) *reinterpret_cast<float2*>(dst) = make_float2(qs[0], qs[1]);
+                float* dst = mq + ((i * HPD + h) * 4 + k) * RH;
+                if constexpr (RH == 4) *reinterpret_cast<float4*>(dst) = make_float4(qs[0], qs[1], qs[2], qs[3]);
+                else if constexpr (RH == 2) *reinterpret_cast<float2*>(dst) = make_float2(qs[0], qs[1]);
                 else dst[0] = qs[0];
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        float acc[kTok][RH];
+#pragma unroll
+        for (int s = 0; s < kTok; ++s)
+#pragma unroll
+            for (int r = 0; r < RH; ++r) acc[s][r] = 0.0f;
 #pragma unroll
         for (int i = 0; i < WPW; ++i) {
 #pragma unroll
             for (int h = 0; h < HPD; ++h) {
-                float b[4][NR];
-                const float* src = mq + (i * HPD + h) * 4 * NR;
-                if constexpr (NR == 2) {
-                    const float4 t0 = *reinterpret_cast<const float4*>(src), t1 = *reinterpret_cast<const float4*>(src + 4);
-                    b[0][0] = t0.x; b[0][1] = t0.y; b[1][0] = t0.z; b[1][1] = t0.w;
-                    b[2][0] = t1.x; b[2][1] = t1.y; b[3][0] = t1.z; b[3][1] = t1.w;
-                } else {
-                    const float4 t0 = *reinterpret_cast<const float4*>(src);
-                    b[0][0] = t0.x; b[1][0] = t0.y; b[2][0] = t0.z; b[3][0] = t0.w;
+                float b[4][RH];
+                const float* src = mq + (i * HPD + h) * 4 * RH;
+#pragma unroll
+                for (int v = 0; v < RH; ++v) {   // RH 16-byte reads cover [4 channel classes][RH rows]
+                    const float4 t = *reinterpret_cast<const float4*>(src + 4 * v);
+                    const float tv[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) b[(4 * v + e) / RH][(4 * v + e) % RH] = tv[e];
                 }
                 float f[kTok][4];
 #pragma unroll
@@ -159,7 +182,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
                     f[s][3] = cvt_ubyte<3>(mk);
                 }
 #pragma unroll
-                for (int r = 0; r < NR; ++r)
+                for (int r = 0; r < RH; ++r)
 #pragma unroll
                     for (int s = 0; s < kTok; ++s) {
                         acc[s][r] = __builtin_fmaf(f[s][0], b[0][r], acc[s][r]);
@@ -169,105 +192,64 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
                     }
             }
         }
-    } else {
+        // the zero-point term of this wave's channels: sum over the quad's four channel classes
 #pragma unroll
-    for (int i = 0; i < WPW; ++i) {
-        const int W = wave * WPW + i;
-        float qv[NR][HPD];
+        for (int r = 0; r < RH; ++r) {
+            float v = qz[r];
+            v += dpp_move<0xB1>(v);   // quad lanes 1 apart
+            v += dpp_move<0x4E>(v);   // quad lanes 2 apart
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+            for (int s = 0; s < kTok; ++s) acc[s][r] += v;
+        }
+        // swap partial sums (the area is this wave's own: its multiplier reads are behind it)
 #pragma unroll
-            for (int j = 0; j < HPD / 4; ++j) {
-                const float4 t = *reinterpret_cast<const float4*>(&qfq[r][k][HPD * W + 4 * j]);
-                qv[r][4 * j] = t.x; qv[r][4 * j + 1] = t.y; qv[r][4 * j + 2] = t.z; qv[r][4 * j + 3] = t.w;
+        for (int s = 0; s < kTok; ++s)
+#pragma unroll
+            for (int r = 0; r < RH; ++r) wsm[wave][(s * RH + r) * 64 + lane] = acc[s][r];
+        __syncthreads();
+        if constexpr (kRowSplit) {
+            // one KV head per query head, two rows: wave = (row, half of the lane's tokens), so that
+            // logits and keys leave as 16-byte stores; the keys are the speculative row's alone
+            const int r = wave & 1, hf = wave >> 1;
+            float o[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int s = 4 * hf + t;
+                float v = wsm[0][(s * RH + r) * 64 + lane];
+#pragma unroll
+                for (int w = 1; w < kScoreWaves; ++w) v += wsm[w][(s * RH + r) * 64 + lane];
+                o[t] = v;
             }
-#pragma unroll
-        for (int h = 0; h < HPD; ++h) {
-            // multiplier of channel 4*(HPD*W + h) + k for every query row
-            const uint32_t m = comp(mt[i][h / 4], h % 4);
-            float sc, z;
-            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), sc, z);
-            // the codes of mask h arrive scaled by 2^(BITS*h)
-            const float sf = sc * __uint_as_float((uint32_t)(127 - BITS * h) << 23);
-            float qs[NR];
-#pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                qs[r] = qv[r][h] * sf;
-                qz[r] = __builtin_fmaf(qv[r][h], z, qz[r]);
+            if (active) {
+                const int i4 = sub * kBlockTokens + kTok * k + 4 * hf;
+                *reinterpret_cast<float4*>(logits + ((size_t)row * NR + r) * logit_stride + i4) = make_float4(o[0], o[1], o[2], o[3]);
+                if (r == NROWS - 1)
+                    *reinterpret_cast<uint4*>(keys + (size_t)row * key_stride + i4) =
+                        make_uint4(float_to_key(o[0]), float_to_key(o[1]), float_to_key(o[2]), float_to_key(o[3]));
             }
-            float f[kTok][4];
+        } else {
 #pragma unroll
-            for (int s = 0; s < kTok; ++s) {
-                const uint32_t mk = comp(cw[i][s / 4], s % 4) & (MASK << (BITS * h));
-                f[s][0] = cvt_ubyte<0>(mk);
-                f[s][1] = cvt_ubyte<1>(mk);
-                f[s][2] = cvt_ubyte<2>(mk);
-                f[s][3] = cvt_ubyte<3>(mk);
-            }
+            for (int r = 0; r < RH; ++r) {
+                float o[TPW];
 #pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                const float b0 = quad_bcast<0>(qs[r]), b1 = quad_bcast<1>(qs[r]);
-                const float b2 = quad_bcast<2>(qs[r]), b3 = quad_bcast<3>(qs[r]);
+                for (int t = 0; t < TPW; ++t) {
+                    const int s = TPW * wave + t;
+                    float v = wsm[0][(s * RH + r) * 64 + lane];
 #pragma unroll
-                for (int s = 0; s < kTok; ++s) {
-                    acc[s][r] = __builtin_fmaf(f[s][0], b0, acc[s][r]);
-                    acc[s][r] = __builtin_fmaf(f[s][1], b1, acc[s][r]);
-                    acc[s][r] = __builtin_fmaf(f[s][2], b2, acc[s][r]);
-                    acc[s][r] = __builtin_fmaf(f[s][3], b3, acc[s][r]);
+                    for (int w = 1; w < kScoreWaves; ++w) v += wsm[w][(s * RH + r) * 64 + lane];
+                    o[t] = v;
+                    if ((r0 + r) % NROWS == NROWS - 1) best[t] = fmaxf(best[t], v);
                 }
+                static_assert(TPW == 2, "one 8-byte store per lane and row");
+                if (active)
+                    *reinterpret_cast<float2*>(logits + ((size_t)row * NR + r0 + r) * logit_stride + i0) = make_float2(o[0], o[1]);
             }
         }
+        if (r0 + RH < NR) __syncthreads();   // partial sums consumed before the next pass reuses the area
     }
-
-    }
-
-    // waves 1.. hand their partial sums to wave 0
-    if (wave > 0) {
-#pragma unroll
-        for (int s = 0; s < kTok; ++s)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) wsm[wave][(s * NR + r) * 64 + lane] = acc[s][r];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) wsm[wave][(kTok * NR + r) * 64 + lane] = qz[r];
-    }
-    __syncthreads();
-    if (wave > 0) return;
-#pragma unroll
-    for (int w = 1; w < kScoreWaves; ++w) {
-#pragma unroll
-        for (int s = 0; s < kTok; ++s)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) acc[s][r] += wsm[w][(s * NR + r) * 64 + lane];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) qz[r] += wsm[w][(kTok * NR + r) * 64 + lane];
-    }
-    // the zero-point term: sum over the quad's four channel classes
-#pragma unroll
-    for (int r = 0; r < NR; ++r) {
-        qz[r] += __shfl_xor(qz[r], 1, 64);
-        qz[r] += __shfl_xor(qz[r], 2, 64);
-    }
-
-    if (active) {
-        const int i0 = sub * kBlockTokens + kTok * k;          // first of this lane's 8 consecutive tokens
-        float best[kTok];
-#pragma unroll
-        for (int s = 0; s < kTok; ++s) best[s] = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            float o[kTok];
-#pragma unroll
-            for (int s = 0; s < kTok; ++s) {
-                o[s] = acc[s][r] + qz[r];
-                if (r % NROWS == NROWS - 1) best[s] = fmaxf(best[s], o[s]);
-            }
-            float4* dst = reinterpret_cast<float4*>(logits + ((size_t)row * NR + r) * logit_stride + i0);
-            dst[0] = make_float4(o[0], o[1], o[2], o[3]);
-            dst[1] = make_float4(o[4], o[5], o[6], o[7]);
-        }
-        uint4* kd = reinterpret_cast<uint4*>(keys + (size_t)row * key_stride + i0);
-        kd[0] = make_uint4(float_to_key(best[0]), float_to_key(best[1]), float_to_key(best[2]), float_to_key(best[3]));
-        kd[1] = make_uint4(float_to_key(best[4]), float_to_key(best[5]), float_to_key(best[6]), float_to_key(best[7]));
+    if constexpr (!kRowSplit) {
+        if (active)
+            *reinterpret_cast<uint2*>(keys + (size_t)row * key_stride + i0) = make_uint2(float_to_key(best[0]), float_to_key(best[1]));
     }
 }
 
