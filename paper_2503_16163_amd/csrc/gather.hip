@@ -12,13 +12,13 @@
 namespace specache {
 namespace {
 
-// A workgroup moves 64 pairs per trip: 8 groups of 32 lanes, each group 8 pairs, and
-// every lane issues its 8 host reads before the first store.  The grid is kept small and
+// A workgroup moves 24 pairs per trip: 8 groups of 32 lanes, each group 3 pairs, and
+// every lane issues its 3 host reads before the first store.  The grid is kept small and
 // loops over the index list: the number of host reads in flight is what matters for the
 // link, and a bounded number of them leaves the memory system's request queues to the
 // attention kernels that run beside the gather.
-constexpr int kPairsPerTrip = 64;
-constexpr int kInFlight = 8;
+constexpr int kInFlight = 3;
+constexpr int kPairsPerTrip = 8 * kInFlight;
 
 __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ host, int max_seq, int k, int total,
                                                      const int32_t* __restrict__ idx, uint4* __restrict__ slot,
@@ -51,9 +51,13 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream) {
     const int total = L.rows * L.topk;
-    // 16 workgroups = 512 KB of host reads in flight: about 80 % of the link rate while the
-    // attention kernels beside it keep most of their HBM rate (measured on MI355X; 64 or more
-    // workgroups reach the link rate but slow those kernels threefold).
+    // 16 workgroups x 3 reads per lane = 192 KB of host reads in flight, about the link's
+    // bandwidth-delay product.  Measured on MI355X at 32 heads x 256 pairs per layer: more
+    // reads in flight shorten the gather (85 us alone with 8 per lane) but slow the attention
+    // kernel beside it by more than that (from 34 us to 54 us with 8 per lane, to 90 us with 32
+    // workgroups), also when the gather's workgroups have their compute units to themselves;
+    // fewer leave the link idle.  This shape gave the shortest whole step there, and gathers
+    // of 16 MB and more per call still run at the link's rate for 512-byte rows (53 GB/s).
     constexpr int kMaxGrid = 16;
     int grid = (total + kPairsPerTrip - 1) / kPairsPerTrip;
     if (grid > kMaxGrid) grid = kMaxGrid;
