@@ -76,7 +76,7 @@ struct AttendArgs {
     const uint16_t* v_spec;
     float* part_o;             // [rows][max_chunks][NR][128]
     float* part_ml;            // [rows][max_chunks][NR][2]
-    int max_chunks, n_main, N, Nq;
+    int max_chunks, n_main, n_chunks, N, Nq;
     float sm_scale;
 };
 
@@ -173,7 +173,18 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     bool* src_spec = reinterpret_cast<bool*>(smem + kLg + kXq + kXp);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int row = blockIdx.y, chunk = blockIdx.x;
+    // The 16-bit chunks are chains of dependent loads: they are dispatched first (all rows), the
+    // quantised chunks after them.
+    const int n_extra = A.n_chunks - A.n_main, rows = L.rows;
+    int row, chunk;
+    if ((int)blockIdx.x < rows * n_extra) {
+        row = blockIdx.x / n_extra;
+        chunk = A.n_main + blockIdx.x % n_extra;
+    } else {
+        const int id = blockIdx.x - rows * n_extra;
+        row = id / A.n_main;
+        chunk = id % A.n_main;
+    }
     float m_row[NR], l_row[NR];
     float* po = A.part_o + (((size_t)row * A.max_chunks + chunk) * NR) * kD;
     float* pml = A.part_ml + (((size_t)row * A.max_chunks + chunk) * NR) * 2;
@@ -208,11 +219,27 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 meta[tt][0] = t2.x; meta[tt][1] = t2.y;
             }
         }
-        // prefetched positions of this chunk, as a bitmap
+        // the first value codes of this thread, needed only after the softmax phase
+        uint4 w4_first = make_uint4(0, 0, 0, 0);
+        if (tid < units) w4_first = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
+        // prefetched positions of this chunk, as a bitmap (the first entries of the index list
+        // are requested with the other loads)
+        constexpr int kIdxUpfront = 2;
+        int sidx[kIdxUpfront];
+#pragma unroll
+        for (int u = 0; u < kIdxUpfront; ++u) {
+            const int j = tid + u * kThreads;
+            sidx[u] = (A.slot_idx && j < L.topk) ? A.slot_idx[(size_t)row * L.topk + j] : -1;
+        }
         if (tid < CH / 32) maskbits[tid] = 0u;
         __syncthreads();
         if (A.slot_idx) {
-            for (int j = tid; j < L.topk; j += kThreads) {
+#pragma unroll
+            for (int u = 0; u < kIdxUpfront; ++u) {
+                const int t = sidx[u] - c0;
+                if (sidx[u] >= 0 && t >= 0 && t < n) atomicOr(&maskbits[t >> 5], 1u << (t & 31));
+            }
+            for (int j = tid + kIdxUpfront * kThreads; j < L.topk; j += kThreads) {
                 const int t = A.slot_idx[(size_t)row * L.topk + j] - c0;
                 if (t >= 0 && t < n) atomicOr(&maskbits[t >> 5], 1u << (t & 31));
             }
@@ -350,8 +377,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             for (int j = 0; j < CPB; ++j)
 #pragma unroll
                 for (int r = 0; r < RH; ++r) acc[j][r] = 0.0f;
-            uint4 w4 = make_uint4(0, 0, 0, 0);
-            if (tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
+            uint4 w4 = w4_first;
+            if (r0 > 0 && tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
             for (int u = tid; u < units; u += kThreads) {
                 const int blk = u / LPB;
                 uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
@@ -415,6 +442,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
         const int n_ex = ks + n_res + (A.k_spec ? 1 : 0);
         const int x0 = (chunk - A.n_main) * kExtraChunk;
         const int n = (n_ex - x0) < kExtraChunk ? (n_ex - x0) : kExtraChunk;
+        // requested together with the query rows: the position of this thread's staged candidate
+        const int t_staged = (tid < n && x0 + tid < ks) ? A.slot_idx[(size_t)row * L.topk + x0 + tid] : -1;
         for (int e = tid; e < NR * kD; e += kThreads)
             qf[e / kD][e % kD] = widen16<BF16>(A.q[((size_t)row * NR) * kD + e]) * A.sm_scale;
         __syncthreads();
@@ -425,7 +454,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             const uint16_t* kp = nullptr;
             bool spec = false;
             if (x < ks) {
-                const int t = A.slot_idx[(size_t)row * L.topk + x];
+                const int t = t_staged;
                 if (t >= 0 && t < A.Nq) kp = A.slot + ((size_t)row * L.topk + x) * 256;
             } else if (x < ks + n_res) {
                 const int t = A.Nq + (x - ks);
@@ -481,18 +510,28 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 }
             }
         }
+        // sum_x p_x V[x][c]: thread = (channel pair, quarter of the candidates), loads in batches of 8,
+        // the first batch requested before the softmax (every candidate with a pair, whatever
+        // its weight turns out to be)
+        const int cp = tid % 64, quarter = tid / 64;
+        constexpr int kPerQuarter = kExtraChunk / 4;
+        uint32_t vw0[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int xl = quarter * kPerQuarter + u;
+            const uint16_t* vp = xl < n ? src_v[xl] : nullptr;
+            vw0[u] = vp ? *reinterpret_cast<const uint32_t*>(vp + 2 * cp) : 0u;
+        }
         __syncthreads();
         chunk_softmax<NR, CHX>(lg, n, red, m_row, l_row);
 
-        // sum_x p_x V[x][c]: thread = (channel pair, quarter of the candidates), loads in batches of 8
-        const int cp = tid % 64, quarter = tid / 64;
         float acc[NR][2];
 #pragma unroll
         for (int r = 0; r < NR; ++r) acc[r][0] = acc[r][1] = 0.0f;
-        constexpr int kPerQuarter = kExtraChunk / 4;
 #pragma unroll
         for (int b0 = 0; b0 < kPerQuarter; b0 += 8) {
             uint32_t vw[8];
+            bool use[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int xl = quarter * kPerQuarter + b0 + u;
@@ -501,13 +540,15 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 #pragma unroll
                     for (int r = 0; r < NR; ++r) any = any || lg[r][xl] != 0.0f;
                 }
-                // weight 0 (also every unused staging entry): its memory is never read
-                vw[u] = any ? *reinterpret_cast<const uint32_t*>(src_v[xl] + 2 * cp) : 0u;
+                use[u] = any;
+                // weight 0 (also every unused staging entry): its memory is never read after the first batch
+                if (b0 == 0) vw[u] = vw0[u];
+                else vw[u] = any ? *reinterpret_cast<const uint32_t*>(src_v[xl] + 2 * cp) : 0u;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int xl = quarter * kPerQuarter + b0 + u;
-                if (xl < n) {
+                if (xl < n && use[u]) {
                     const float v0 = widen16<BF16>(vw[u] & 0xFFFFu), v1 = widen16<BF16>(vw[u] >> 16);
 #pragma unroll
                     for (int r = 0; r < NR; ++r) {
@@ -562,6 +603,16 @@ __global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const f
     const int row = blockIdx.x / NR, r = blockIdx.x % NR;
     const float* ml = part_ml + ((size_t)row * max_chunks * NR + r) * 2;
     const size_t ml_stride = (size_t)NR * 2;
+    // the first batch of partial outputs is requested before anything depends on the maxima
+    const int cp = lane, slice = wave;
+    const float2* po = reinterpret_cast<const float2*>(part_o + ((size_t)row * max_chunks * NR + r) * kD) + cp;
+    const size_t po_stride = (size_t)NR * kD / 2;
+    float2 v0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int ch = slice + kCombineSlices * u;
+        v0[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
+    }
     float mloc = -INFINITY;
     for (int ch = tid; ch < n_chunks; ch += kCombineThreads) {
         const float m = ml[ch * ml_stride];
@@ -587,16 +638,14 @@ __global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const f
     float den = 0.0f;
 #pragma unroll
     for (int w = 0; w < kCombineSlices; ++w) den += red[kCombineSlices + w];
-    const int cp = lane, slice = wave;
-    const float2* po = reinterpret_cast<const float2*>(part_o + ((size_t)row * max_chunks * NR + r) * kD) + cp;
-    const size_t po_stride = (size_t)NR * kD / 2;
     float2 o = make_float2(0.f, 0.f);
     for (int c0 = slice; c0 < n_chunks; c0 += kCombineSlices * 8) {
         float2 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int ch = c0 + kCombineSlices * u;
-            v[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
+            if (c0 == slice) v[u] = v0[u];
+            else v[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -627,7 +676,7 @@ template <int BITS, int GROUP, int G, int NROWS>
 hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* out, hipStream_t stream) {
     constexpr int NR = G * NROWS;
     if (A.n_main + n_extra > kCombineMaxChunks) return hipErrorInvalidValue;
-    const dim3 grid(A.n_main + n_extra, L.rows), block(kThreads);
+    const dim3 grid((A.n_main + n_extra) * L.rows), block(kThreads);
     if (L.bf16)
         hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, true>), grid, block, 0, stream, L, A);
     else
@@ -645,6 +694,7 @@ hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, floa
     if (L.G == g_ && n_rows == n_) {                                            \
         A.n_main = (A.Nq + main_chunk(g_ * n_) - 1) / main_chunk(g_ * n_);      \
         const int n_extra = (n_ex + kExtraChunk - 1) / kExtraChunk;             \
+        A.n_chunks = A.n_main + n_extra;                                        \
         if (A.n_main + n_extra > A.max_chunks) return hipErrorInvalidValue;     \
         return launch3<BITS, GROUP, g_, n_>(L, A, n_extra, out, stream);        \
     }
@@ -675,6 +725,7 @@ hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, i
     A.part_ml = scratch.part_ml;
     A.max_chunks = scratch.max_chunks;
     A.n_main = 0;
+    A.n_chunks = 0;
     A.N = N;
     A.Nq = Nq;
     A.sm_scale = sm_scale;

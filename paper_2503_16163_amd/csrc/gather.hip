@@ -12,12 +12,12 @@
 namespace specache {
 namespace {
 
-// A workgroup moves 24 pairs per trip: 8 groups of 32 lanes, each group 3 pairs, and
-// every lane issues its 3 host reads before the first store.  The grid is kept small and
+// A workgroup moves 32 pairs per trip: 8 groups of 32 lanes, each group 4 pairs, and
+// every lane issues its 4 host reads before the first store.  The grid is kept small and
 // loops over the index list: the number of host reads in flight is what matters for the
 // link, and a bounded number of them leaves the memory system's request queues to the
 // attention kernels that run beside the gather.
-constexpr int kInFlight = 3;
+constexpr int kInFlight = 4;
 constexpr int kPairsPerTrip = 8 * kInFlight;
 
 __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ host, int max_seq, int k, int total,
@@ -51,13 +51,14 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream) {
     const int total = L.rows * L.topk;
-    // 16 workgroups x 3 reads per lane = 192 KB of host reads in flight, about the link's
-    // bandwidth-delay product.  Measured on MI355X at 32 heads x 256 pairs per layer: more
-    // reads in flight shorten the gather (85 us alone with 8 per lane) but slow the attention
-    // kernel beside it by more than that (from 34 us to 54 us with 8 per lane, to 90 us with 32
-    // workgroups), also when the gather's workgroups have their compute units to themselves;
-    // fewer leave the link idle.  This shape gave the shortest whole step there, and gathers
-    // of 16 MB and more per call still run at the link's rate for 512-byte rows (53 GB/s).
+    // 16 workgroups x 4 reads per lane = 256 KB of host reads in flight.  Measured on MI355X at
+    // 32 heads x 256 pairs per layer: beside the other kernels of the step the link delivers
+    // about 40 GB/s whatever the number of reads in flight (alone: 49 GB/s with 8 per lane, the
+    // rate for 512-byte rows), while every further read in flight slows the attention kernel
+    // that runs beside the gather (29 us alone, 37 us with 3 per lane, 41 with 4, 49 with 8, 65
+    // with 32 workgroups), also when the gather's workgroups have their compute units to
+    // themselves.  With 4 the gather, which then bounds the step, is as fast as it gets and the
+    // kernels of the main stream still fit beside it.
     constexpr int kMaxGrid = 16;
     int grid = (total + kPairsPerTrip - 1) / kPairsPerTrip;
     if (grid > kMaxGrid) grid = kMaxGrid;
