@@ -613,12 +613,17 @@ __global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const f
         const int ch = slice + kCombineSlices * u;
         v0[u] = ch < n_chunks ? po[ch * po_stride] : make_float2(0.f, 0.f);
     }
-    float mloc = -INFINITY;
-    for (int ch = tid; ch < n_chunks; ch += kCombineThreads) {
-        const float m = ml[ch * ml_stride];
-        wgt[ch] = m;
-        mloc = fmaxf(mloc, m);
+    // (max, sum) of this thread's chunks: one 8-byte load each, all requested at once
+    constexpr int kMlPerThread = (kCombineMaxChunks + kCombineThreads - 1) / kCombineThreads;
+    float2 mlv[kMlPerThread];
+#pragma unroll
+    for (int u = 0; u < kMlPerThread; ++u) {
+        const int ch = tid + u * kCombineThreads;
+        mlv[u] = ch < n_chunks ? *reinterpret_cast<const float2*>(ml + ch * ml_stride) : make_float2(-INFINITY, 0.0f);
     }
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kMlPerThread; ++u) mloc = fmaxf(mloc, mlv[u].x);
     mloc = wave_max(mloc);
     if (lane == 0) red[wave] = mloc;
     __syncthreads();
@@ -626,11 +631,14 @@ __global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const f
 #pragma unroll
     for (int w = 1; w < kCombineSlices; ++w) mmax = fmaxf(mmax, red[w]);
     float dloc = 0.0f;
-    for (int ch = tid; ch < n_chunks; ch += kCombineThreads) {
-        const float m = wgt[ch];
-        const float w = m == -INFINITY ? 0.0f : __expf(m - mmax);
-        wgt[ch] = w;
-        dloc = __builtin_fmaf(ml[ch * ml_stride + 1], w, dloc);
+#pragma unroll
+    for (int u = 0; u < kMlPerThread; ++u) {
+        const int ch = tid + u * kCombineThreads;
+        if (ch < n_chunks) {
+            const float w = mlv[u].x == -INFINITY ? 0.0f : __expf(mlv[u].x - mmax);
+            wgt[ch] = w;
+            dloc = __builtin_fmaf(mlv[u].y, w, dloc);
+        }
     }
     dloc = wave_sum(dloc);
     if (lane == 0) red[kCombineSlices + wave] = dloc;
