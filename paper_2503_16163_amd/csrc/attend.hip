@@ -40,6 +40,18 @@ __device__ __forceinline__ float cvt_ubyte(uint32_t w) {
 
 __device__ __forceinline__ uint32_t comp(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
+// Operands of v_mfma_f32_16x16x32_f16: lane l holds A[l % 16][8 (l / 16) .. + 7] and
+// B[8 (l / 16) .. + 7][l % 16] as eight f16, and C[4 (l / 16) .. + 3][l % 16] as four floats.
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+// two bytes of w, each widened to 16 bits: a small integer n read as f16 is the subnormal n * 2^-24
+template <int HI>
+__device__ __forceinline__ uint32_t bytes_to_halves(uint32_t w) {
+    return __builtin_amdgcn_perm(0u, w, HI ? 0x0c030c02u : 0x0c010c00u);
+}
+
 // Wave-wide reductions on the VALU: four DPP steps leave every lane with its 16-lane row's
 // result, the four row results are then read as scalars.  (A butterfly of ds_bpermute
 // shuffles costs an LDS round trip per step.)
@@ -162,6 +174,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     __shared__ float red[kWaves * NR * (1 + M)];
     __shared__ float red_sum[kWaves * NR];
     __shared__ float red_z[kWaves * NR * M];
+    __shared__ float red_scale[kWaves];
     __shared__ uint32_t maskbits[CH / 32];
 
     float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
@@ -284,6 +297,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
         float* zl = o_lds + CH * kPl;            // [CH][M]
         static_assert(!kSplit || CH * kPl + CH * M <= kOl, "p and z planes must fit the merged-output area");
         float zacc[NR][M], sloc[NR];
+        float sc_max = 0.0f;     // largest value scale of this thread's tokens (MFMA path: operand scaling)
 #pragma unroll
         for (int r = 0; r < NR; ++r) {
             sloc[r] = 0.0f;
@@ -306,7 +320,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 for (int m = 0; m < M; ++m) {
                     float sc, z;
                     derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
-                    if constexpr (kSplit) zl[i * M + m] = z;
+                    if constexpr (kSplit) {
+                        zl[i * M + m] = z;
+                        sc_max = fmaxf(sc_max, sc);
+                    }
 #pragma unroll
                     for (int r = 0; r < NR; ++r) {
                         ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
@@ -316,6 +333,10 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             }
         }
         if constexpr (kSplit) {
+            {
+                const float v = wave_max(sc_max);
+                if (lane == 0) red_scale[wave] = v;
+            }
             __syncthreads();
             constexpr int S = 64 / NR;                    // slices per row inside a wave
             constexpr int T = (CH / kWaves) / S;          // tokens per lane
@@ -369,71 +390,173 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             l_row[r] = v;
         }
 
-        // sum_i (p_i s_i) code[i][c] for this lane's CPB channels, RH query rows per pass (with
-        // more than four rows the accumulators of all rows at once would halve the occupancy)
-        for (int r0 = 0; r0 < NR; r0 += RH) {
-            float acc[CPB][RH];
+        if constexpr (kSplit) {
+            // ---- value side on the matrix cores (8 or 16 query rows per KV head) ----
+            // o[r][c] = sum_i code[i][c] * ps[i][m(c)][r] per 32-token block is a 16 x 32 x 16 product:
+            // A = codes (rows: 16 channels of one value group, columns: 32 tokens), read from the
+            // packed bytes as f16 subnormals (code << (8 - BITS), i.e. code * 2^(8 - BITS - 24), exact);
+            // B = ps scaled by a power of two near the top of the f16 range and split into
+            // hi + lo f16 (columns: (row r, hi | lo)), C accumulates in fp32.  Wave w owns the 32
+            // channels 32 w .. 32 w + 31 (two tiles, one value group), so no sums cross waves.
+            constexpr int NT = NR / 8;                      // column tiles of 8 query rows x (hi, lo)
+            constexpr int JT = CPB / 2;                     // codes of one byte that go to one tile
+            constexpr int LW = 32 / CPB;                    // code lanes (bytes per token) of this wave's channels
+            const int ic = lane & 15, kq = lane >> 4;
+            const int Lrow = wave * LW + ic % LW;           // code lane of this A row; row's bit = BITS * (JT t + ic / LW)
+            const int mw = (32 * wave) / GROUP;             // value group of this wave's channels
+            float smax = red_scale[0];
 #pragma unroll
-            for (int j = 0; j < CPB; ++j)
+            for (int w = 1; w < kWaves; ++w) smax = fmaxf(smax, red_scale[w]);
+            // 2^(14 - exponent(smax)): the largest p * s (p <= 1) lands in [2^14, 2^15)
+            uint32_t eb = (__float_as_uint(smax) >> 23) & 0xFFu;
+            eb = eb < 15u ? 15u : (eb > 240u ? 240u : eb);
+            const float bscale = __uint_as_float((268u - eb) << 23);
+            float4v acc[2][NT];
 #pragma unroll
-                for (int r = 0; r < RH; ++r) acc[j][r] = 0.0f;
-            uint4 w4 = w4_first;
-            if (r0 > 0 && tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
-            for (int u = tid; u < units; u += kThreads) {
-                const int blk = u / LPB;
-                uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
-                if (u + kThreads < units)
-                    w4n = *reinterpret_cast<const uint4*>(vc_lane + (size_t)((u + kThreads) / LPB) * code_block_bytes(BITS));
-                const int hb = blk * 2 + within / (16 * BITS);   // 16-token half block inside the chunk
-                const float* psb = ps + (hb * M + mgrp) * kCell + r0;
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int dq = 0; dq < 4; ++dq) {
-                    const uint32_t w = comp(w4, dq);
-                    float pv[4][RH];
+                for (int nt = 0; nt < NT; ++nt) acc[t][nt] = float4v{0.f, 0.f, 0.f, 0.f};
+            // every code is lifted to the top bits of its byte before it is widened: the matrix
+            // cores do not normalise subnormal inputs before they align the products of a dot
+            // product, so a code left in the low bits (two significant bits under eight leading
+            // zeros) loses the low end of its small products (measured: 3e-5 of the sum for codes
+            // at bit 0, 2e-7 at bit 6)
+            uint32_t amask[2], ashift[2];
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
+            for (int t = 0; t < 2; ++t) {
+                const int j = JT * t + ic / LW;
+                amask[t] = MASK << (BITS * j);
+                ashift[t] = (8 - BITS) - BITS * j;
+            }
+            const int nblk = n / kBlockTokens;
+            // 8 tokens of code lane Lrow: half block kq / 2, bytes 8 (kq % 2) .. + 7
+            const uint8_t* a_lane = vc_row + ((size_t)(kq >> 1) * (16 * BITS) + Lrow) * 16 + 8 * (kq & 1);
+            uint2 aw = make_uint2(0, 0);
+            if (nblk > 0) aw = *reinterpret_cast<const uint2*>(a_lane);
+            for (int b = 0; b < nblk; ++b) {
+                uint2 awn = make_uint2(0, 0);
+                if (b + 1 < nblk) awn = *reinterpret_cast<const uint2*>(a_lane + (size_t)(b + 1) * code_block_bytes(BITS));
+                // B: column (r, hi | lo) = lane % 16, tokens 32 b + 8 kq .. + 7
+                const int i0 = b * kBlockTokens + 8 * kq;
+                const float* psb = ps + ((i0 >> 4) * M + mw) * kCell + (i0 & 15) * NR;
+                uint4v bop[NT];
 #pragma unroll
-                        for (int r = 0; r < RH; ++r) pv[b][r] = psb[(dq * 4 + b) * NR + r];
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int r = 8 * nt + (ic >> 1);
+                    float x[8];
 #pragma unroll
-                    for (int j = 0; j < CPB; ++j) {
-                        const uint32_t mk = w & (MASK << (BITS * j));
-                        const float f0 = cvt_ubyte<0>(mk), f1 = cvt_ubyte<1>(mk), f2 = cvt_ubyte<2>(mk), f3 = cvt_ubyte<3>(mk);
+                    for (int e = 0; e < 8; ++e) x[e] = psb[e * NR + r] * bscale;
+                    uint32_t hw[4];
 #pragma unroll
-                        for (int r = 0; r < RH; ++r) {
-                            acc[j][r] = __builtin_fmaf(f0, pv[0][r], acc[j][r]);
-                            acc[j][r] = __builtin_fmaf(f1, pv[1][r], acc[j][r]);
-                            acc[j][r] = __builtin_fmaf(f2, pv[2][r], acc[j][r]);
-                            acc[j][r] = __builtin_fmaf(f3, pv[3][r], acc[j][r]);
-                        }
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        // hi by truncation, lo = x - hi rounded: hi + lo is x to 2^-21
+                        const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x[2 * e2], x[2 * e2 + 1]));
+                        const float h0 = widen16<false>(hi & 0xFFFFu), h1 = widen16<false>(hi >> 16);
+                        const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x[2 * e2] - h0, x[2 * e2 + 1] - h1));
+                        hw[e2] = (ic & 1) ? lo : hi;
+                    }
+                    bop[nt] = uint4v{hw[0], hw[1], hw[2], hw[3]};
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const uint32_t m0 = (aw.x & amask[t]) << ashift[t], m1 = (aw.y & amask[t]) << ashift[t];
+                    const uint4v aop{bytes_to_halves<0>(m0), bytes_to_halves<1>(m0), bytes_to_halves<0>(m1), bytes_to_halves<1>(m1)};
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[t][nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, aop), __builtin_bit_cast(half8, bop[nt]),
+                                                                             acc[t][nt], 0, 0, 0);
+                }
+                aw = awn;
+            }
+            // C rows 4 kq + v of tile t are A rows (channels), C column = (r, hi | lo): add the lo
+            // column to its hi neighbour, undo the two scalings, add the zero-point term, store
+            const float unscale = __uint_as_float((127u + 24u + eb - 141u) << 23);   // 2^24 / bscale
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int r = 8 * nt + (ic >> 1);
+                    float zsum = 0.0f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) zsum += red_z[(w * NR + r) * M + mw];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        float val = acc[t][nt][v];
+                        val += dpp_move<kDppXor1>(val);
+                        const int row16 = 4 * kq + v;                    // A row inside the tile
+                        const int j = JT * t + row16 / LW;               // code index inside its byte
+                        const int c = (wave * LW + row16 % LW) * CPB + j;
+                        val = val * (unscale * __uint_as_float((uint32_t)(127 - (8 - BITS)) << 23)) + zsum;
+                        if ((ic & 1) == 0) po[r * kD + c] = val;
                     }
                 }
-                w4 = w4n;
-            }
-            // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
-#pragma unroll
-            for (int j = 0; j < CPB; ++j)
-#pragma unroll
-                for (int r = 0; r < RH; ++r) {
-                    float v = acc[j][r] * __uint_as_float((uint32_t)(127 - BITS * j) << 23);
-#pragma unroll
-                    for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
-                    acc[j][r] = v;
-                }
-            if constexpr (!kSplit) __syncthreads();   // o_lds shares the region with ps: everyone is done with ps
-            if (lane < 16 * BITS) {
-#pragma unroll
+        } else {
+            // sum_i (p_i s_i) code[i][c] for this lane's CPB channels, RH query rows per pass (with
+            // more than four rows the accumulators of all rows at once would halve the occupancy)
+            for (int r0 = 0; r0 < NR; r0 += RH) {
+                float acc[CPB][RH];
+    #pragma unroll
                 for (int j = 0; j < CPB; ++j)
-#pragma unroll
-                    for (int r = 0; r < RH; ++r) o_lds[((size_t)wave * NR + r0 + r) * kD + Lc * CPB + j] = acc[j][r];
+    #pragma unroll
+                    for (int r = 0; r < RH; ++r) acc[j][r] = 0.0f;
+                uint4 w4 = w4_first;
+                if (r0 > 0 && tid < units) w4 = *reinterpret_cast<const uint4*>(vc_lane + (size_t)(tid / LPB) * code_block_bytes(BITS));
+                for (int u = tid; u < units; u += kThreads) {
+                    const int blk = u / LPB;
+                    uint4 w4n = make_uint4(0, 0, 0, 0);   // next iteration's codes, in flight during this one's arithmetic
+                    if (u + kThreads < units)
+                        w4n = *reinterpret_cast<const uint4*>(vc_lane + (size_t)((u + kThreads) / LPB) * code_block_bytes(BITS));
+                    const int hb = blk * 2 + within / (16 * BITS);   // 16-token half block inside the chunk
+                    const float* psb = ps + (hb * M + mgrp) * kCell + r0;
+    #pragma unroll
+                    for (int dq = 0; dq < 4; ++dq) {
+                        const uint32_t w = comp(w4, dq);
+                        float pv[4][RH];
+    #pragma unroll
+                        for (int b = 0; b < 4; ++b)
+    #pragma unroll
+                            for (int r = 0; r < RH; ++r) pv[b][r] = psb[(dq * 4 + b) * NR + r];
+    #pragma unroll
+                        for (int j = 0; j < CPB; ++j) {
+                            const uint32_t mk = w & (MASK << (BITS * j));
+                            const float f0 = cvt_ubyte<0>(mk), f1 = cvt_ubyte<1>(mk), f2 = cvt_ubyte<2>(mk), f3 = cvt_ubyte<3>(mk);
+    #pragma unroll
+                            for (int r = 0; r < RH; ++r) {
+                                acc[j][r] = __builtin_fmaf(f0, pv[0][r], acc[j][r]);
+                                acc[j][r] = __builtin_fmaf(f1, pv[1][r], acc[j][r]);
+                                acc[j][r] = __builtin_fmaf(f2, pv[2][r], acc[j][r]);
+                                acc[j][r] = __builtin_fmaf(f3, pv[3][r], acc[j][r]);
+                            }
+                        }
+                    }
+                    w4 = w4n;
+                }
+                // codes arrived scaled by 2^(BITS*j); lanes with equal Lc hold the same channels
+    #pragma unroll
+                for (int j = 0; j < CPB; ++j)
+    #pragma unroll
+                    for (int r = 0; r < RH; ++r) {
+                        float v = acc[j][r] * __uint_as_float((uint32_t)(127 - BITS * j) << 23);
+    #pragma unroll
+                        for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
+                        acc[j][r] = v;
+                    }
+                if constexpr (!kSplit) __syncthreads();   // o_lds shares the region with ps: everyone is done with ps
+                if (lane < 16 * BITS) {
+    #pragma unroll
+                    for (int j = 0; j < CPB; ++j)
+    #pragma unroll
+                        for (int r = 0; r < RH; ++r) o_lds[((size_t)wave * NR + r0 + r) * kD + Lc * CPB + j] = acc[j][r];
+                }
             }
-        }
-        __syncthreads();
-        for (int e = tid; e < NR * kD; e += kThreads) {
-            const int r = e / kD, c = e % kD;
-            float v = 0.0f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) v += o_lds[((size_t)w * NR + r) * kD + c] + red_z[(w * NR + r) * M + c / GROUP];
-            po[e] = v;
+            __syncthreads();
+            for (int e = tid; e < NR * kD; e += kThreads) {
+                const int r = e / kD, c = e % kD;
+                float v = 0.0f;
+    #pragma unroll
+                for (int w = 0; w < kWaves; ++w) v += o_lds[((size_t)w * NR + r) * kD + c] + red_z[(w * NR + r) * M + c / GROUP];
+                po[e] = v;
+            }
         }
     } else {
         // ------------------------------------------------------------ 16-bit candidates
