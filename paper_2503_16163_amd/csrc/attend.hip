@@ -26,7 +26,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kExtraChunk = 128;
 
-__host__ __device__ constexpr int main_chunk(int NR) { return NR <= 4 ? 512 : NR <= 8 ? 256 : 128; }
+__host__ __device__ constexpr int main_chunk(int NR) { return NR <= 8 ? 512 : 256; }
 
 template <int B>
 __device__ __forceinline__ float cvt_ubyte(uint32_t w) {
@@ -152,24 +152,26 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
     constexpr uint32_t MASK = ((1u << BITS) - 1u) * 0x01010101u;
     constexpr int CHX = CH > kExtraChunk ? CH : kExtraChunk;
     constexpr int TPT = (CH + kThreads - 1) / kThreads;   // chunk tokens per thread
-    // one region: ps[M][CH][NR] (main chunks) or lg[NR][CHX] (extra chunks); reused as
-    // o_lds[kWaves][NR][128] at the end
+    // With up to four query rows the value side runs on the vector ALUs, with more on the matrix
+    // cores (kSplit).  One LDS region serves, in turn: for main chunks ps[M][CH][NR] (vector
+    // path) or the planes p[CH][NR+1], z[CH][M], s[CH][M] (matrix path); for extra chunks
+    // lg[NR][CHX] and their tables; at the end o_lds[kWaves][NR][128] (vector path, extra chunks).
     // ps is stored in cells [16-token half block][value group m] of 16*NR floats plus one
     // 16-byte pad: the lanes of one LDS read differ only in (half block, m), i.e. in
     // consecutive cells, and the pad spreads those over distinct banks.
+    constexpr bool kSplit = NR > 4;
     constexpr int kCell = 16 * NR + 4;
-    constexpr int kLg = NR * CHX, kPs = (CH / 16) * M * kCell, kOl = kWaves * NR * kD;
+    constexpr int kPl = NR + 1;              // row pitch of the p plane: lanes of one read in distinct banks
+    constexpr int kPlanes = CH * kPl + 2 * CH * M;
+    constexpr int kLg = NR * CHX, kPs = kSplit ? kPlanes : (CH / 16) * M * kCell, kOl = kWaves * NR * kD;
     // the extra chunks' tables (query rows, candidate pointers) live behind lg in the same region:
     // a workgroup is either a main or an extra chunk, and LDS per workgroup decides how many
     // chunks are resident per compute unit
     constexpr int kXq = NR * kD, kXp = 2 * kExtraChunk * 2 /* two pointer tables, 8 B each */, kXs = kExtraChunk / 4;
     constexpr int kExtra = kLg + kXq + kXp + kXs;
     constexpr int kMax1 = kExtra > kPs ? kExtra : kPs;
-    // with more than four query rows the value loop runs in passes of four rows and the merged
-    // outputs need LDS of their own while ps is still in use
-    constexpr bool kSplit = NR > 4;
-    constexpr int RH = kSplit ? 4 : NR;
-    constexpr int kRegion = kSplit ? kMax1 + kOl : (kMax1 > kOl ? kMax1 : kOl);
+    constexpr int RH = NR;
+    constexpr int kRegion = kMax1 > kOl ? kMax1 : kOl;
     __shared__ __attribute__((aligned(16))) float smem[kRegion];
     __shared__ float red[kWaves * NR * (1 + M)];
     __shared__ float red_sum[kWaves * NR];
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 
     float (*lg)[CHX] = reinterpret_cast<float (*)[CHX]>(smem);
     float* ps = smem;                        // [CH/16][M] cells
-    float* o_lds = kSplit ? smem + kMax1 : smem;   // [kWaves][NR][128]
+    float* o_lds = smem;                     // [kWaves][NR][128]
     float (*qf)[kD] = reinterpret_cast<float (*)[kD]>(smem + kLg);
     const uint16_t** src_k = reinterpret_cast<const uint16_t**>(smem + kLg + kXq);
     const uint16_t** src_v = src_k + kExtraChunk;
@@ -292,10 +294,9 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
         // sums, too many wave reductions: p and z go to LDS instead (in the area the merged
         // outputs use later) and the lanes re-read them as (row, slice of this wave's tokens), so
         // that only the slices of a row are left to add up.
-        constexpr int kPl = NR + 1;              // row pitch of the p plane: lanes of one read in distinct banks
-        float* pl = o_lds;                       // [CH][kPl]
-        float* zl = o_lds + CH * kPl;            // [CH][M]
-        static_assert(!kSplit || CH * kPl + CH * M <= kOl, "p and z planes must fit the merged-output area");
+        float* pl = smem;                        // [CH][kPl]
+        float* zl = pl + CH * kPl;               // [CH][M]
+        float* sl = zl + CH * M;                 // [CH][M]
         float zacc[NR][M], sloc[NR];
         float sc_max = 0.0f;     // largest value scale of this thread's tokens (MFMA path: operand scaling)
 #pragma unroll
@@ -322,12 +323,14 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                     derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
                     if constexpr (kSplit) {
                         zl[i * M + m] = z;
+                        sl[i * M + m] = sc;
                         sc_max = fmaxf(sc_max, sc);
-                    }
+                    } else {
 #pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
-                        if constexpr (!kSplit) zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                        for (int r = 0; r < NR; ++r) {
+                            ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
+                            zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
+                        }
                     }
                 }
             }
@@ -395,8 +398,8 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             // o[r][c] = sum_i code[i][c] * ps[i][m(c)][r] per 32-token block is a 16 x 32 x 16 product:
             // A = codes (rows: 16 channels of one value group, columns: 32 tokens), read from the
             // packed bytes as f16 subnormals (code << (8 - BITS), i.e. code * 2^(8 - BITS - 24), exact);
-            // B = ps scaled by a power of two near the top of the f16 range and split into
-            // hi + lo f16 (columns: (row r, hi | lo)), C accumulates in fp32.  Wave w owns the 32
+            // B = ps = p * s (from the planes), scaled by a power of two near the top of the f16
+            // range and split into hi + lo f16 (columns: (row r, hi | lo)), C accumulates in fp32.  Wave w owns the 32
             // channels 32 w .. 32 w + 31 (two tiles, one value group), so no sums cross waves.
             constexpr int NT = NR / 8;                      // column tiles of 8 query rows x (hi, lo)
             constexpr int JT = CPB / 2;                     // codes of one byte that go to one tile
@@ -438,14 +441,16 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 if (b + 1 < nblk) awn = *reinterpret_cast<const uint2*>(a_lane + (size_t)(b + 1) * code_block_bytes(BITS));
                 // B: column (r, hi | lo) = lane % 16, tokens 32 b + 8 kq .. + 7
                 const int i0 = b * kBlockTokens + 8 * kq;
-                const float* psb = ps + ((i0 >> 4) * M + mw) * kCell + (i0 & 15) * NR;
+                float sv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sv[e] = sl[(i0 + e) * M + mw] * bscale;
                 uint4v bop[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     const int r = 8 * nt + (ic >> 1);
                     float x[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = psb[e * NR + r] * bscale;
+                    for (int e = 0; e < 8; ++e) x[e] = pl[(i0 + e) * kPl + r] * sv[e];
                     uint32_t hw[4];
 #pragma unroll
                     for (int e2 = 0; e2 < 4; ++e2) {
@@ -541,7 +546,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                         for (int mask = 32; mask >= 16 * BITS; mask >>= 1) v += __shfl_xor(v, mask, 64);
                         acc[j][r] = v;
                     }
-                if constexpr (!kSplit) __syncthreads();   // o_lds shares the region with ps: everyone is done with ps
+                __syncthreads();   // o_lds shares the region with ps: everyone is done with ps
                 if (lane < 16 * BITS) {
     #pragma unroll
                     for (int j = 0; j < CPB; ++j)
