@@ -205,6 +205,21 @@ def main():
         "frac": score_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "traffic": None, "algorithmic_bytes": score_bytes, "avg_us": score_us,
     }
+    # Second view of the same kernel: it is bound by vector-ALU issue (one wave64 instruction per 4 clocks per
+    # SIMD), so its instruction count (rocprofv3 --pmc SQ_INSTS_VALU, profiles/valu.json) over its measured
+    # duration is set against 256 CUs x 4 SIMDs x 2.4 GHz / 4.
+    roofline_alu = None
+    vpath = os.path.join(ROOT, "profiles", "valu.json")
+    try:
+        n_valu = json.load(open(vpath)).get(args.workload, {}).get("score_kernel")
+        if n_valu and score_us:
+            peak = 256 * 4 * 2.4e9 / 4 / 1e9
+            ach = n_valu / (score_us * 1e-6) / 1e9
+            roofline_alu = {"bound": "alu", "kernel": "score_kernel", "achieved": round(ach, 1), "peak": round(peak, 1),
+                            "unit": "G wave64 vector instructions/s", "frac": round(ach / peak, 3),
+                            "instructions_per_launch": n_valu}
+    except Exception:
+        roofline_alu = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
@@ -229,6 +244,7 @@ def main():
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "kernel_us_no_gather": per_kernel_ng,
         "hbm_gbs_layer": round(layer_bytes / (us_layer * 1e-6) / 1e9, 1),
+        "roofline_alu": roofline_alu,
         "kernel_us": breakdown,
         "prefill_quant_offload": prefill,
         "attend_hbm_gbs": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),

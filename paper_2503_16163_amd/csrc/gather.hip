@@ -12,17 +12,16 @@
 namespace specache {
 namespace {
 
-// A workgroup moves 32 pairs per trip: 8 groups of 32 lanes, each group 4 pairs, and
-// every lane issues its 4 host reads before the first store.  The grid is kept small and
+// A workgroup moves 8 * kInFlight pairs per trip: 8 groups of 32 lanes, each group kInFlight
+// pairs, and every lane issues its kInFlight host reads before the first store.  The grid is kept small and
 // loops over the index list: the number of host reads in flight is what matters for the
 // link, and a bounded number of them leaves the memory system's request queues to the
 // attention kernels that run beside the gather.
-constexpr int kInFlight = 4;
-constexpr int kPairsPerTrip = 8 * kInFlight;
-
+template <int kInFlight>
 __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ host, int max_seq, int k, int total,
                                                      const int32_t* __restrict__ idx, uint4* __restrict__ slot,
                                                      int32_t* __restrict__ slot_idx) {
+    constexpr int kPairsPerTrip = 8 * kInFlight;
     const int part = threadIdx.x % 32, grp = threadIdx.x / 32;
     for (int base = blockIdx.x * kPairsPerTrip; base < total; base += gridDim.x * kPairsPerTrip) {
         int src[kInFlight];
@@ -48,7 +47,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 
 }  // namespace
 
-hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
+hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream) {
     const int total = L.rows * L.topk;
     // 16 workgroups x 4 reads per lane = 256 KB of host reads in flight.  Measured on MI355X at
@@ -59,11 +58,22 @@ hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot,
     // with 32 workgroups), also when the gather's workgroups have their compute units to
     // themselves.  With 4 the gather, which then bounds the step, is as fast as it gets and the
     // kernels of the main stream still fit beside it.
+    // Where a pair stands for much scoring and attention work (long rows, several query heads per
+    // KV head, few pairs: 131 k keys x 4 heads per 1024 pairs in the long-context configuration)
+    // the gather has time to spare and two reads per lane disturb the other kernels less: whole
+    // step 160 us instead of 174 us there, while the configurations with fewer than 384 scored
+    // keys per fetched pair are slower with two.
     constexpr int kMaxGrid = 16;
-    int grid = (total + kPairsPerTrip - 1) / kPairsPerTrip;
+    const bool light = (double)L.rows * L.G * Nq >= 384.0 * total;
+    const int per_trip = 8 * (light ? 2 : 4);
+    int grid = (total + per_trip - 1) / per_trip;
     if (grid > kMaxGrid) grid = kMaxGrid;
-    hipLaunchKernelGGL(gather_kernel, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk, total,
-                       idx, (uint4*)slot, slot_idx);
+    if (light)
+        hipLaunchKernelGGL(gather_kernel<2>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
+                           total, idx, (uint4*)slot, slot_idx);
+    else
+        hipLaunchKernelGGL(gather_kernel<4>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
+                           total, idx, (uint4*)slot, slot_idx);
     return hipGetLastError();
 }
 

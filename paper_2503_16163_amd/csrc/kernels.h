@@ -45,8 +45,9 @@ int topk_parts(int Nq, int k);   // ranges a row of Nq keys is split into (1 = s
 hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key_stride, int32_t* idx_out,
                        const TopkScratch& scratch, hipStream_t stream);
 
-// gather rows idx[row][j] of the host store into slot [rows][k][256] and slot_idx [rows][k]
-hipError_t launch_gather(const LayerView& L, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
+// gather rows idx[row][j] of the host store into slot [rows][k][256] and slot_idx [rows][k];
+// Nq (quantised positions of the layer) only paces the transfer
+hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream);
 
 // attend: partial pass + combine.  slot/slot_idx may be null (nothing prefetched).

@@ -322,7 +322,7 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
     {
         TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
-        SPC_HIP(ctx, launch_gather(L.view, idx, L.slot[slot], L.slot_idx[slot], st));
+        SPC_HIP(ctx, launch_gather(L.view, L.Nq, idx, L.slot[slot], L.slot_idx[slot], st));
     }
     SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
     L.slot_filled[slot] = true;
