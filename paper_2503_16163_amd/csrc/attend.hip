@@ -14,8 +14,12 @@
 //
 // Values are quantised per token over g channels, so for the main chunks
 //   sum_i p_i V'[i][c] = sum_i (p_i s[i][m]) code[i][c] + sum_i p_i z[i][m],  m = c / g.
-// A lane owns 8/BITS channels and reads 16 tokens of them as one 16-byte load;
-// p_i s[i][m] comes from LDS (computed once per token by the softmax phase).
+// With up to four query rows per KV head the first sum runs on the vector ALUs: a lane owns
+// 8/BITS channels and reads 16 tokens of them as one 16-byte load; p_i s[i][m] comes from
+// LDS (computed once per token by the softmax phase).  With 8 or 16 rows it is a dense
+// enough contraction for the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulation):
+// the codes enter as f16 subnormals straight from the packed bytes, p_i s[i][m] as a
+// hi + lo pair of f16.
 #include "kernels.h"
 #include "layout.h"
 
@@ -496,8 +500,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                     }
                 }
         } else {
-            // sum_i (p_i s_i) code[i][c] for this lane's CPB channels, RH query rows per pass (with
-            // more than four rows the accumulators of all rows at once would halve the occupancy)
+            // sum_i (p_i s_i) code[i][c] for this lane's CPB channels, all (at most four) query rows
             for (int r0 = 0; r0 < NR; r0 += RH) {
                 float acc[CPB][RH];
     #pragma unroll

@@ -100,6 +100,24 @@ def test_long_row_topk_in_two_launches_keeps_the_tie_rule():
         c.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g", [(8, 2, synth.BF16, 2, 64), (8, 2, synth.FP16, 1, 32), (8, 1, synth.BF16, 2, 32)])
+def test_matrix_core_value_path_keeps_fp32_accuracy(Hq, Hkv, dtype, bits, g):
+    """With 8 or 16 query rows per KV head the value side of attend runs on the matrix cores with f16 operands
+    (codes as subnormals, p*s split into hi + lo).  That has to stay as accurate as the fp32 vector path (errors
+    of a few 1e-6): an operand split that loses its low part, or codes left in the low bits of their subnormal,
+    shows as a few 1e-4, far inside the 2e-3 bar but a defect all the same."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 3000, dtype, bits, g, 64, seed=4100 + bits * 10 + g)
+    try:
+        c.load()
+        for t in range(2):
+            c.append_token(t)
+            c.decode_step()
+        assert c.stats["max_out_err"] < 5e-5, c.stats
+    finally:
+        c.close()
+
+
 def test_streamed_load_equals_bulk_load():
     """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
     from tests.harness import Case
