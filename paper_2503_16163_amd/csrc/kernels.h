@@ -34,6 +34,11 @@ hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void*
 hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
 
+// the same for 8 or 16 query rows per KV head, on the matrix cores
+bool score_uses_matrix_cores(int G, int n_rows);
+hipError_t launch_score_mfma(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
+                             size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
+
 // top-k over keys[row][0..Nq): idx_out [rows][k], ascending, -1 padded.  Rows too long for one
 // workgroup's registers are selected in two launches through the candidate buffers.
 struct TopkScratch {

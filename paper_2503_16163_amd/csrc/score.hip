@@ -284,6 +284,8 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream) {
     if (Nq <= 0) return hipSuccess;
     if (L.group != 32 && L.group != 64) return hipErrorInvalidValue;
+    if (score_uses_matrix_cores(L.G, n_rows))
+        return launch_score_mfma(L, q, n_rows, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);
     if (L.bits == 2) return launch2<2>(L, q, n_rows, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);
     if (L.bits == 1) return launch2<1>(L, q, n_rows, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);
     return hipErrorInvalidValue;
