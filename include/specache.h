@@ -63,7 +63,8 @@ typedef struct specache_config {
     int32_t residual;   /* R: multiple of g, g <= R <= 256.  Tokens are appended one at
                            a time; when N - Nq reaches R the oldest g unquantised
                            tokens are quantised.  The paper uses 64.                   */
-    int32_t max_seq;    /* capacity in tokens per (batch, KV head), multiple of 64     */
+    int32_t max_seq;    /* capacity in tokens per (batch, KV head), multiple of 64;
+                           at most about 650000 (320000 with 8 query heads per KV head) */
     int32_t topk;       /* k: 1 .. 4096                                                */
     int32_t dtype;      /* SPECACHE_FP16 or SPECACHE_BF16: type of K, V, q and C       */
     float sm_scale;     /* logit scale; <= 0 selects 1/sqrt(head_dim)                  */

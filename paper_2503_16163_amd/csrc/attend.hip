@@ -321,13 +321,14 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                     if constexpr (kSplit) pl[i * kPl + r] = p[r];
                     else sloc[r] += p[r];
                 }
+                float scv[M], zv[M];
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     float sc, z;
                     derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
+                    scv[m] = sc;
+                    zv[m] = z;
                     if constexpr (kSplit) {
-                        zl[i * M + m] = z;
-                        sl[i * M + m] = sc;
                         sc_max = fmaxf(sc_max, sc);
                     } else {
 #pragma unroll
@@ -335,6 +336,15 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                             ps[((i >> 4) * M + m) * kCell + (i & 15) * NR + r] = p[r] * sc;
                             zacc[r][m] = __builtin_fmaf(p[r], z, zacc[r][m]);
                         }
+                    }
+                }
+                if constexpr (kSplit) {   // one vector store per plane and token
+                    if constexpr (M == 4) {
+                        *reinterpret_cast<float4*>(&zl[i * M]) = make_float4(zv[0], zv[1], zv[2], zv[3]);
+                        *reinterpret_cast<float4*>(&sl[i * M]) = make_float4(scv[0], scv[1], scv[2], scv[3]);
+                    } else {
+                        *reinterpret_cast<float2*>(&zl[i * M]) = make_float2(zv[0], zv[1]);
+                        *reinterpret_cast<float2*>(&sl[i * M]) = make_float2(scv[0], scv[1]);
                     }
                 }
             }
@@ -354,7 +364,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             for (int m = 0; m < M; ++m) za[m] = 0.0f;
 #pragma unroll
             for (int j = 0; j < T; ++j) {
-                const int i = wave * (CH / kWaves) + slice * T + j;
+                const int i = wave * (CH / kWaves) + j * S + slice;   // slices interleaved: one read's lanes in distinct banks
                 if (i < n) {
                     const float pr = pl[i * kPl + r];
                     sa += pr;
@@ -847,6 +857,7 @@ hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, floa
 
 int attend_main_chunk_tokens(int NR) { return main_chunk(NR); }
 int attend_extra_chunk_tokens() { return kExtraChunk; }
+int attend_max_chunks() { return kCombineMaxChunks; }
 
 hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
                          const float* logits, size_t logit_stride, const uint16_t* slot, const int32_t* slot_idx,

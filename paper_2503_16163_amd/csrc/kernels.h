@@ -63,6 +63,7 @@ struct AttendScratch {
 };
 int attend_main_chunk_tokens(int NR);
 int attend_extra_chunk_tokens();
+int attend_max_chunks();   // chunks per row the merge kernel handles
 hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
                          const float* logits, size_t logit_stride, const uint16_t* slot,
                          const int32_t* slot_idx, const void* k_spec, const void* v_spec,

@@ -166,6 +166,18 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (c.max_seq < 64 || c.max_seq % 64) return fail(nullptr, SPECACHE_EINVAL, "max_seq must be a positive multiple of 64");
     if (c.topk < 1 || c.topk > 4096) return fail(nullptr, SPECACHE_EINVAL, "topk must be in [1, 4096]");
     if (c.dtype != SPECACHE_FP16 && c.dtype != SPECACHE_BF16) return fail(nullptr, SPECACHE_EINVAL, "dtype must be fp16 or bf16");
+    {
+        // attend splits a row into chunks whose partial results one workgroup merges
+        int most = 0;
+        for (int n = 1; n <= 2; ++n) {
+            const int ch = attend_main_chunk_tokens(G * n), ec = attend_extra_chunk_tokens();
+            const int chunks = (c.max_seq + ch - 1) / ch + (c.topk + c.residual + 1 + ec - 1) / ec;
+            most = chunks > most ? chunks : most;
+        }
+        if (most > attend_max_chunks())
+            return fail(nullptr, SPECACHE_EINVAL, "max_seq is beyond what attend splits into chunks (about 650000 tokens, "
+                                                  "320000 with 8 query heads per KV head)");
+    }
 
     specache_ctx* ctx = new (std::nothrow) specache_ctx();
     if (!ctx) return fail(nullptr, SPECACHE_ENOMEM, "host allocation failed");

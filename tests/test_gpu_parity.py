@@ -197,6 +197,9 @@ def test_all_positions_prefetched_matches_full_attention():
 
 
 def test_error_paths():
+    with pytest.raises(binding.SpeCacheError) as ei:        # rejected before anything is allocated
+        binding.SpeCache(1, 1, 8, 1, 2, 32, 64 * 20000, 16, synth.FP16)
+    assert ei.value.code == binding.EINVAL
     sc = binding.SpeCache(2, 1, 2, 2, 2, 32, 256, 16, synth.FP16)
     try:
         k = torch.zeros((1, 2, 300, 128), dtype=torch.float16, device="cuda")
