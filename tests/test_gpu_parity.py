@@ -118,6 +118,26 @@ def test_matrix_core_value_path_keeps_fp32_accuracy(Hq, Hkv, dtype, bits, g):
         c.close()
 
 
+@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128)])
+def test_long_decode_crosses_flushes(bits, g, R):
+    """70 decode steps from a short prompt: the residual ring wraps and groups are flushed during decoding
+    (every g steps), each step checked against the oracle, the whole quantised prefix and the offloaded rows
+    at the end."""
+    from tests.harness import Case
+    c = Case(1, 4, 2, 200, synth.FP16, bits, g, 24, R=R, seed=6100 + g)
+    try:
+        c.load()
+        n0, nq0 = c.check_quantized()
+        for t in range(70):
+            c.append_token(t)
+            c.decode_step()
+        n1, nq1 = c.check_quantized()
+        assert n1 == n0 + 70 and nq1 >= nq0 + 64 - (64 % g)
+        c.check_offload(first=c.S, count=70)
+    finally:
+        c.close()
+
+
 def test_streamed_load_equals_bulk_load():
     """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
     from tests.harness import Case
