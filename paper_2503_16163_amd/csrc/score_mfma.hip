@@ -70,28 +70,42 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(LayerView L, co
     const int row = blockIdx.y, tile = blockIdx.x;
     const int n_sub = Nq / kBlockTokens;
 
-    // this lane's multipliers-to-be: sm_scale * q[r][32 kc + 8 kq + e] for its column's row r
-    float qreg[NT][4][8];
-    float qabs[NT];
+    // This lane's multipliers-to-be.  Column (r, hi | lo) needs sm_scale * q[r][32 kc + 8 kq + e],
+    // e = 0..7, per chunk; the two lanes of a column pair share that work, the hi lane taking
+    // e = 0..3 and the lo lane e = 4..7, and swap halves of their operands afterwards.  The
+    // values are kept scaled by a power of two chosen from the row's largest |q| (|q'| < 2^7).
+    const int hl = ic & 1;
+    float qreg[NT][4][4];
+    float q_unscale[NT];                       // the inverse of that power of two
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int r = 8 * nt + (ic >> 1);
         const uint16_t* qr = q + ((size_t)row * NR + r) * kD;
-        qabs[nt] = 0.0f;
+        float qa = 0.0f;
 #pragma unroll
         for (int kc = 0; kc < 4; ++kc) {
-            const uint4 w = *reinterpret_cast<const uint4*>(qr + 32 * kc + 8 * kq);
-            const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
+            const uint2 w = *reinterpret_cast<const uint2*>(qr + 32 * kc + 8 * kq + 4 * hl);
+            const uint32_t wd[2] = {w.x, w.y};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
+            for (int e = 0; e < 4; ++e) {
                 const float v = widen16<BF16>((wd[e / 2] >> (16 * (e % 2))) & 0xFFFFu) * sm_scale;
                 qreg[nt][kc][e] = v;
-                qabs[nt] = fmaxf(qabs[nt], fabsf(v));
+                qa = fmaxf(qa, fabsf(v));
             }
         }
-        // largest |q| of the row: over the four lanes of the column
-        qabs[nt] = fmaxf(qabs[nt], __shfl_xor(qabs[nt], 16, 64));
-        qabs[nt] = fmaxf(qabs[nt], __shfl_xor(qabs[nt], 32, 64));
+        // largest |q| of the row: over the pair and the four lanes of the column
+        qa = fmaxf(qa, __shfl_xor(qa, 1, 64));
+        qa = fmaxf(qa, __shfl_xor(qa, 16, 64));
+        qa = fmaxf(qa, __shfl_xor(qa, 32, 64));
+        const uint32_t eq = (__float_as_uint(qa) >> 23) & 0xFFu;       // |q| < 2^(eq - 126)
+        int fq = 260 - (int)eq;                                        // field of 2^(133 - eq)
+        fq = fq < 100 ? 100 : (fq > 224 ? 224 : fq);
+        const float qscale = __uint_as_float((uint32_t)fq << 23);
+        q_unscale[nt] = __uint_as_float((uint32_t)(254 - fq) << 23);
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) qreg[nt][kc][e] *= qscale;
     }
 
     // code bits of this lane's 8 channels of a 32-channel chunk: channel 32 kc + 8 kq + e is code
@@ -142,51 +156,56 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(LayerView L, co
             float s0, z0, s1, z1;
             derive_scale_zero<BITS>(widen16<BF16>(m0 & 0xFFFFu), widen16<BF16>(m0 >> 16), s0, z0);
             derive_scale_zero<BITS>(widen16<BF16>(m1 & 0xFFFFu), widen16<BF16>(m1 >> 16), s1, z1);
+            // the table holds s scaled by a power of two chosen from the group's largest s (s' < 2^8),
+            // so that q' s' < 2^15 sits near the top of the f16 range
+            const float smax = wave_max_nonneg(fmaxf(s0, s1));
+            const uint32_t es = (__float_as_uint(smax) >> 23) & 0xFFu;     // s < 2^(es - 126)
+            int fs = 261 - (int)es;                                        // field of 2^(134 - es)
+            fs = fs < 100 ? 100 : (fs > 224 ? 224 : fs);
+            const float sscale = __uint_as_float((uint32_t)fs << 23);
+            const float s_unscale = __uint_as_float((uint32_t)(254 - fs) << 23) * (kUnlift * 16777216.0f);   // 2^24 / (s scale 2^(8-BITS))
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // earlier reads of the table are done
             __builtin_amdgcn_wave_barrier();
-            *reinterpret_cast<float2*>(&sz[wave][0][2 * lane]) = make_float2(s0, s1);
+            *reinterpret_cast<float2*>(&sz[wave][0][2 * lane]) = make_float2(s0 * sscale, s1 * sscale);
             *reinterpret_cast<float2*>(&sz[wave][1][2 * lane]) = make_float2(z0, z1);
-            const float smax = wave_max_nonneg(fmaxf(s0, s1));
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const uint32_t es = (__float_as_uint(smax) >> 23) & 0xFFu;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                // |q s| < 2^(eq + es - 252): scale so that it stays below 2^15
-                const uint32_t eq = (__float_as_uint(qabs[nt]) >> 23) & 0xFFu;
-                int eb = 394 - (int)eq - (int)es;
-                eb = eb < 30 ? 30 : (eb > 253 ? 253 : eb);
-                const float bscale = __uint_as_float((uint32_t)eb << 23);
-                unscale[nt] = __uint_as_float((uint32_t)(254 - eb) << 23) * (kUnlift * 16777216.0f);   // 2^24 / (bscale 2^(8-BITS))
+                unscale[nt] = q_unscale[nt] * s_unscale;
                 float zacc = 0.0f;
 #pragma unroll
                 for (int kc = 0; kc < 4; ++kc) {
-                    const float4 sa = *reinterpret_cast<const float4*>(&sz[wave][0][32 * kc + 8 * kq]);
-                    const float4 sb = *reinterpret_cast<const float4*>(&sz[wave][0][32 * kc + 8 * kq + 4]);
-                    const float4 za = *reinterpret_cast<const float4*>(&sz[wave][1][32 * kc + 8 * kq]);
-                    const float4 zb = *reinterpret_cast<const float4*>(&sz[wave][1][32 * kc + 8 * kq + 4]);
-                    const float sv[8] = {sa.x, sa.y, sa.z, sa.w, sb.x, sb.y, sb.z, sb.w};
-                    const float zv[8] = {za.x, za.y, za.z, za.w, zb.x, zb.y, zb.z, zb.w};
-                    uint32_t hw[4];
+                    const float4 sa = *reinterpret_cast<const float4*>(&sz[wave][0][32 * kc + 8 * kq + 4 * hl]);
+                    const float4 za = *reinterpret_cast<const float4*>(&sz[wave][1][32 * kc + 8 * kq + 4 * hl]);
+                    const float sv[4] = {sa.x, sa.y, sa.z, sa.w};
+                    const float zv[4] = {za.x, za.y, za.z, za.w};
+                    uint32_t keep[2], send[2];
 #pragma unroll
-                    for (int e2 = 0; e2 < 4; ++e2) {
+                    for (int e2 = 0; e2 < 2; ++e2) {
                         const float q0 = qreg[nt][kc][2 * e2], q1 = qreg[nt][kc][2 * e2 + 1];
                         zacc = __builtin_fmaf(q0, zv[2 * e2], zacc);
                         zacc = __builtin_fmaf(q1, zv[2 * e2 + 1], zacc);
-                        const float x0 = q0 * sv[2 * e2] * bscale, x1 = q1 * sv[2 * e2 + 1] * bscale;
+                        const float x0 = q0 * sv[2 * e2], x1 = q1 * sv[2 * e2 + 1];
                         // hi by truncation, lo = x - hi: hi + lo is x to 2^-21
                         const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x0, x1));
                         const float h0f = widen16<false>(hi & 0xFFFFu), h1f = widen16<false>(hi >> 16);
                         const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x0 - h0f, x1 - h1f));
-                        hw[e2] = (ic & 1) ? lo : hi;
+                        // the hi lane keeps its hi halves and hands its lo halves to the lo lane, and vice versa
+                        keep[e2] = hl ? lo : hi;
+                        send[e2] = hl ? hi : lo;
                     }
-                    bop[nt][kc] = uint4v{hw[0], hw[1], hw[2], hw[3]};
+                    const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send[0], kDppXor1, 0xf, 0xf, true);
+                    const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send[1], kDppXor1, 0xf, 0xf, true);
+                    // k-slots 0..3 come from the hi lane's channels, 4..7 from the lo lane's
+                    bop[nt][kc] = hl ? uint4v{r0, r1, keep[0], keep[1]} : uint4v{keep[0], keep[1], r0, r1};
                 }
-                // the zero-point term of (row, group): the four lanes of the column hold a quarter each
+                // the zero-point term of (row, group): the pair and the four lanes of the column hold a share each
+                zacc += dpp_move<kDppXor1>(zacc);
                 zacc += __shfl_xor(zacc, 16, 64);
                 zacc += __shfl_xor(zacc, 32, 64);
-                qz[nt] = zacc;
+                qz[nt] = zacc * q_unscale[nt];
             }
         }
 
