@@ -455,26 +455,32 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                 if (b + 1 < nblk) awn = *reinterpret_cast<const uint2*>(a_lane + (size_t)(b + 1) * code_block_bytes(BITS));
                 // B: column (r, hi | lo) = lane % 16, tokens 32 b + 8 kq .. + 7
                 const int i0 = b * kBlockTokens + 8 * kq;
-                float sv[8];
+                // the two lanes of a column share the work: the hi lane splits tokens 0..3, the lo
+                // lane tokens 4..7, then each hands the other the halves of the other's kind
+                const int hl = ic & 1, ih = i0 + 4 * hl;
+                float sv[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sv[e] = sl[(i0 + e) * M + mw] * bscale;
+                for (int e = 0; e < 4; ++e) sv[e] = sl[(ih + e) * M + mw] * bscale;
                 uint4v bop[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     const int r = 8 * nt + (ic >> 1);
-                    float x[8];
+                    float x[4];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = pl[(i0 + e) * kPl + r] * sv[e];
-                    uint32_t hw[4];
+                    for (int e = 0; e < 4; ++e) x[e] = pl[(ih + e) * kPl + r] * sv[e];
+                    uint32_t keep[2], send[2];
 #pragma unroll
-                    for (int e2 = 0; e2 < 4; ++e2) {
+                    for (int e2 = 0; e2 < 2; ++e2) {
                         // hi by truncation, lo = x - hi rounded: hi + lo is x to 2^-21
                         const uint32_t hi = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x[2 * e2], x[2 * e2 + 1]));
                         const float h0 = widen16<false>(hi & 0xFFFFu), h1 = widen16<false>(hi >> 16);
                         const uint32_t lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x[2 * e2] - h0, x[2 * e2 + 1] - h1));
-                        hw[e2] = (ic & 1) ? lo : hi;
+                        keep[e2] = hl ? lo : hi;
+                        send[e2] = hl ? hi : lo;
                     }
-                    bop[nt] = uint4v{hw[0], hw[1], hw[2], hw[3]};
+                    const uint32_t r0 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send[0], kDppXor1, 0xf, 0xf, true);
+                    const uint32_t r1 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send[1], kDppXor1, 0xf, 0xf, true);
+                    bop[nt] = hl ? uint4v{r0, r1, keep[0], keep[1]} : uint4v{keep[0], keep[1], r0, r1};
                 }
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
