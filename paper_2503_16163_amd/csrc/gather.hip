@@ -22,6 +22,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
                                                      const int32_t* __restrict__ idx, uint4* __restrict__ slot,
                                                      int32_t* __restrict__ slot_idx) {
     constexpr int kPairsPerTrip = 8 * kInFlight;
+    __builtin_amdgcn_s_setprio(3);   // a wave's issue priority inside its SIMD, not a stream priority
     const int part = threadIdx.x % 32, grp = threadIdx.x / 32;
     for (int base = blockIdx.x * kPairsPerTrip; base < total; base += gridDim.x * kPairsPerTrip) {
         int src[kInFlight];
@@ -50,29 +51,32 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream) {
     const int total = L.rows * L.topk;
-    // 16 workgroups x 4 reads per lane = 256 KB of host reads in flight.  Measured on MI355X at
-    // 32 heads x 256 pairs per layer: beside the other kernels of the step the link delivers
-    // about 40 GB/s whatever the number of reads in flight (alone: 49 GB/s with 8 per lane, the
-    // rate for 512-byte rows), while every further read in flight slows the attention kernel
-    // that runs beside the gather (29 us alone, 37 us with 3 per lane, 41 with 4, 49 with 8, 65
-    // with 32 workgroups), also when the gather's workgroups have their compute units to
-    // themselves.  With 4 the gather, which then bounds the step, is as fast as it gets and the
-    // kernels of the main stream still fit beside it.
+    // 16 workgroups x 3 reads per lane = 192 KB of host reads in flight, issued at raised wave
+    // priority.  Measured on MI355X at 32 heads x 256 pairs per layer: beside the other kernels
+    // of the step the link delivers 40-46 GB/s (alone: 49 GB/s with 8 reads per lane, the rate
+    // for 512-byte rows), while every further read in flight slows the attention kernel that
+    // runs beside the gather (29 us alone, 38 us with 3 per lane, 41 with 4, 49 with 8, 65 with
+    // 32 workgroups), also when the gather's workgroups have their compute units to themselves.
+    // The gather's few waves issue almost nothing but their host reads; at the default priority
+    // they wait for issue slots behind the scoring waves that share their SIMDs, and the link
+    // idles meanwhile: with s_setprio 3 the gather takes 90 us per layer instead of 104 us.
+    // Three reads per lane then balance the two streams (whole step 100 us per layer; 102 us
+    // with four, 104 us at the default priority); the link-bound configurations lose at most
+    // 1 % against four.
     // Where a pair stands for much scoring and attention work (long rows, several query heads per
     // KV head, few pairs: 131 k keys x 4 heads per 1024 pairs in the long-context configuration)
     // the gather has time to spare and two reads per lane disturb the other kernels less: whole
-    // step 160 us instead of 174 us there, while the configurations with fewer than 384 scored
-    // keys per fetched pair are slower with two.
+    // step 149 us instead of 154 us there.
     constexpr int kMaxGrid = 16;
     const bool light = (double)L.rows * L.G * Nq >= 384.0 * total;
-    const int per_trip = 8 * (light ? 2 : 4);
+    const int per_trip = 8 * (light ? 2 : 3);
     int grid = (total + per_trip - 1) / per_trip;
     if (grid > kMaxGrid) grid = kMaxGrid;
     if (light)
         hipLaunchKernelGGL(gather_kernel<2>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
                            total, idx, (uint4*)slot, slot_idx);
     else
-        hipLaunchKernelGGL(gather_kernel<4>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
+        hipLaunchKernelGGL(gather_kernel<3>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
                            total, idx, (uint4*)slot, slot_idx);
     return hipGetLastError();
 }
