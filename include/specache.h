@@ -132,9 +132,12 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
  * ascending with -1 padding (the format specache_score_topk writes).  Copies
  * the selected (K, V) rows from the pinned host store into staging slot
  * `slot` (0 or 1) of the layer, together with the index list.  Enqueued on
- * side_stream; the library orders it after the specache_score_topk that wrote
- * idx and after the last specache_attend that read this slot, and orders later
- * specache_attend calls on this slot after it, with events of its own.
+ * side_stream; the library orders it after the layer's last specache_score_topk
+ * and after the last specache_attend that read this slot, and orders later
+ * specache_attend calls on this slot after it (stream order where the calls
+ * share a stream, events of its own otherwise).  A stream handed to one of the
+ * hot calls must stay alive until the context is destroyed: a later call may
+ * still record an event on it.
  * Reusing a slot discards what it held (the paper's eviction).
  * Errors: EINVAL (slot not 0/1, null idx, bad layer).
  */

@@ -26,10 +26,20 @@ struct Layer {
     int32_t* slot_idx[2] = {nullptr, nullptr};
     bool slot_filled[2] = {false, false};
     hipEvent_t gathered[2] = {nullptr, nullptr};
+    hipStream_t gather_stream[2] = {nullptr, nullptr};
+    // Ordering of a slot's reader (attend) before its next writer (gather).  An event record costs
+    // the stream about as much as a small kernel, so attend records `attended` only when the later
+    // gather could not be ordered otherwise: an attend enqueued on the stream of the layer's last
+    // score_topk precedes, in that stream, the next score_topk's `idx_ready` record, which every
+    // gather waits for.  The sequence numbers tell whether that record came after the attend.
     hipEvent_t attended[2] = {nullptr, nullptr};
     bool attended_recorded[2] = {false, false};
+    hipStream_t attend_stream[2] = {nullptr, nullptr};
+    uint64_t attend_seq[2] = {0, 0};     // 0: no attend has read the slot
     hipEvent_t idx_ready = nullptr;
     bool idx_ready_recorded = false;
+    hipStream_t idx_ready_stream = nullptr;
+    uint64_t idx_ready_seq = 0;
     const int32_t* last_gather_idx = nullptr;
     int last_gather_slot = -1;
 };
@@ -49,6 +59,7 @@ struct specache_ctx {
     AttendScratch scratch{};
     TopkScratch topk_scratch{};
     int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
+    uint64_t seq = 0;            // counts the calls that order streams (see Layer)
     std::string err;
     // optional per-kernel timing: (start, stop) event pairs recorded around each launch
     bool timing = false;
@@ -317,6 +328,8 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     }
     SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;
+    L.idx_ready_stream = st;
+    L.idx_ready_seq = ++ctx->seq;
     ctx->scored_layer = layer;
     ctx->scored_rows = n_rows;
     ctx->scored_N = L.N;
@@ -330,13 +343,24 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     if (slot != 0 && slot != 1) return fail(ctx, SPECACHE_EINVAL, "slot must be 0 or 1");
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)side_stream;
-    if (L.idx_ready_recorded) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
-    if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
+    if (L.idx_ready_recorded && st != L.idx_ready_stream) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
+    if (L.attend_seq[slot] != 0 && L.attend_stream[slot] != st) {
+        const bool behind_idx_ready = L.idx_ready_recorded && L.attend_stream[slot] == L.idx_ready_stream &&
+                                      L.attend_seq[slot] < L.idx_ready_seq;
+        if (!L.attended_recorded[slot] && !behind_idx_ready) {
+            // a second gather into the slot without a new score_topk in between: record now, on the
+            // attend's stream, which orders this gather after everything enqueued there so far
+            SPC_HIP(ctx, hipEventRecord(L.attended[slot], L.attend_stream[slot]));
+            L.attended_recorded[slot] = true;
+        }
+        if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
+    }
     {
         TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
         SPC_HIP(ctx, launch_gather(L.view, L.Nq, idx, L.slot[slot], L.slot_idx[slot], st));
     }
     SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
+    L.gather_stream[slot] = st;
     L.slot_filled[slot] = true;
     L.last_gather_idx = idx;
     L.last_gather_slot = slot;
@@ -356,7 +380,7 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
     if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
     hipStream_t st = (hipStream_t)stream;
-    if (slot >= 0) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
+    if (slot >= 0 && L.gather_stream[slot] != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
     {
         TimedLaunch t(ctx, st, SPECACHE_K_ATTEND);
         SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
@@ -364,8 +388,13 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
                                    v_spec, ctx->scratch, out, st));
     }
     if (slot >= 0) {
-        SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
-        L.attended_recorded[slot] = true;
+        L.attend_stream[slot] = st;
+        L.attend_seq[slot] = ++ctx->seq;
+        L.attended_recorded[slot] = false;
+        if (!(L.idx_ready_recorded && st == L.idx_ready_stream)) {
+            SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
+            L.attended_recorded[slot] = true;
+        }
     }
     return SPECACHE_OK;
 }

@@ -170,6 +170,43 @@ def test_non_speculative_fetching():
             c.close()
 
 
+def test_slot_reuse_orders_gather_after_attend():
+    """A slot is gathered again (a) without a new selection in between and (b) after an attend that ran on a
+    stream of its own: both orderings go through the library's events rather than through stream order."""
+    from tests.harness import Case, check_out, to_dev
+    c = Case(1, 4, 2, 1500, synth.FP16, 2, 32, 40, seed=2280)
+    try:
+        c.load()
+        c.decode_step()                       # t = 0: gathers into slot 1
+        c.decode_step()                       # t = 1: attend reads slot 1, gathers into slot 0
+        t = 1
+        q_bits = synth.make_queries(c.seed, 1, 4, 128, c.dtype, n_rows=2, sub=t)
+        ks_bits, vs_bits = synth.make_spec_kv(c.seed, 1, 2, 128, c.dtype, sub=t)
+        q, ks, vs = to_dev(q_bits, c.dtype), to_dev(ks_bits, c.dtype), to_dev(vs_bits, c.dtype)
+        main, other = torch.cuda.current_stream(), torch.cuda.Stream()
+        _, nq = c.sc.counts(0)
+        picks = [np.arange(40, dtype=np.int32) * 3 + 1, np.arange(40, dtype=np.int32) * 7 + 2]
+        assert picks[1].max() < nq
+        for rnd, P in enumerate(picks):
+            idx = torch.from_numpy(np.broadcast_to(P, (1, 2, 40)).copy()).cuda()
+            c.sc.gather(0, idx, 1, c.side)    # slot 1 again; the last selection is older than its last attend
+            out = torch.empty((1, 4, 2, 128), dtype=torch.float32, device="cuda")
+            st = main if rnd == 0 else other  # second round: the reader runs on a third stream
+            st.wait_stream(main)
+            c.sc.attend(0, q, 2, ks, vs, 1, out, st)
+            torch.cuda.synchronize()
+            out_h = out.cpu().numpy()
+            for (b, h) in c.sample:
+                ref = c.oc[(b, h)].attend(q_bits[b, h * 2:(h + 1) * 2], c.sm_scale, P=P, k_spec=ks_bits[b, h, 0],
+                                          v_spec=vs_bits[b, h, 0])
+                check_out(out_h[b, h * 2:(h + 1) * 2], ref, what=f"re-gathered slot, round {rnd}, {(b, h)}")
+        idx = torch.from_numpy(np.broadcast_to(picks[0], (1, 2, 40)).copy()).cuda()
+        c.sc.gather(0, idx, 1, c.side)        # after the attend on `other`: waits for its recorded event
+        c.decode_step()                       # t = 2 reads slot 0 and carries on as usual
+    finally:
+        c.close()
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
