@@ -51,33 +51,30 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
                          hipStream_t stream) {
     const int total = L.rows * L.topk;
-    // 16 workgroups x 3 reads per lane = 192 KB of host reads in flight, issued at raised wave
+    // 16 workgroups x 4 reads per lane = 256 KB of host reads in flight, issued at raised wave
     // priority.  Measured on MI355X at 32 heads x 256 pairs per layer: beside the other kernels
     // of the step the link delivers 40-46 GB/s (alone: 49 GB/s with 8 reads per lane, the rate
     // for 512-byte rows), while every further read in flight slows the attention kernel that
-    // runs beside the gather (29 us alone, 38 us with 3 per lane, 41 with 4, 49 with 8, 65 with
+    // runs beside the gather (29 us alone, 38 us with 3 per lane, 43 with 4, 49 with 8, 65 with
     // 32 workgroups), also when the gather's workgroups have their compute units to themselves.
     // The gather's few waves issue almost nothing but their host reads; at the default priority
     // they wait for issue slots behind the scoring waves that share their SIMDs, and the link
     // idles meanwhile: with s_setprio 3 the gather takes 90 us per layer instead of 104 us.
-    // Three reads per lane then balance the two streams (whole step 100 us per layer; 102 us
-    // with four, 104 us at the default priority); the link-bound configurations lose at most
-    // 1 % against four.
-    // Where a pair stands for much scoring and attention work (long rows, several query heads per
-    // KV head, few pairs: 131 k keys x 4 heads per 1024 pairs in the long-context configuration)
-    // the gather has time to spare and two reads per lane disturb the other kernels less: whole
-    // step 149 us instead of 154 us there.
+    // The number of reads per lane follows the work of the main stream per fetched pair (scored
+    // keys x query heads per pair): the more of it, the more the gather has time to spare and the
+    // more a read in flight costs the other kernels.  Whole step, us per layer: 128 keys per pair
+    // (7B shape at 32 k): 92.4 with four reads, 94.6 with three; 256 (4 query heads per KV head,
+    // 32 k keys, 512 pairs): 176 with four, 173.5 with three; 512 (131 k keys, 1024 pairs): 149
+    // with two, 154 with three.
     constexpr int kMaxGrid = 16;
-    const bool light = (double)L.rows * L.G * Nq >= 384.0 * total;
-    const int per_trip = 8 * (light ? 2 : 3);
-    int grid = (total + per_trip - 1) / per_trip;
+    const double keys_per_pair = (double)L.G * Nq / (L.topk > 0 ? L.topk : 1);
+    const int in_flight = keys_per_pair >= 384.0 ? 2 : keys_per_pair >= 192.0 ? 3 : 4;
+    int grid = (total + 8 * in_flight - 1) / (8 * in_flight);
     if (grid > kMaxGrid) grid = kMaxGrid;
-    if (light)
-        hipLaunchKernelGGL(gather_kernel<2>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
-                           total, idx, (uint4*)slot, slot_idx);
-    else
-        hipLaunchKernelGGL(gather_kernel<3>, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk,
-                           total, idx, (uint4*)slot, slot_idx);
+    if (grid < 1) return hipSuccess;
+    const auto kernel = in_flight == 2 ? gather_kernel<2> : in_flight == 3 ? gather_kernel<3> : gather_kernel<4>;
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk, total, idx,
+                       (uint4*)slot, slot_idx);
     return hipGetLastError();
 }
 
