@@ -199,23 +199,26 @@ def main():
     layer_bytes = score_bytes + attend_bytes
     us_layer = ms_per_step * 1e3 / layers
     score_us = per_kernel_us["score"]
+    # which scoring kernel the library launches for this shape (two query rows per query head)
+    score_name = ("score_i8_kernel" if G == 1 and args.variant != "nonspec"
+                  else "score_mfma_kernel" if (G * (1 if args.variant == "nonspec" else 2)) % 8 == 0 else "score_kernel")
     roofline = {
-        "bound": "hbm", "kernel": "score_kernel",
+        "bound": "hbm", "kernel": score_name,
         "achieved": score_bytes / (score_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": score_bytes / (score_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "traffic": None, "algorithmic_bytes": score_bytes, "avg_us": score_us,
     }
-    # Second view of the same kernel: it is bound by vector-ALU issue (one wave64 instruction per 4 clocks per
-    # SIMD), so its instruction count (rocprofv3 --pmc SQ_INSTS_VALU, profiles/valu.json) over its measured
-    # duration is set against 256 CUs x 4 SIMDs x 2.4 GHz / 4.
+    # Second view of the same kernel: its vector instruction count (rocprofv3 --pmc SQ_INSTS_VALU,
+    # profiles/valu.json; matrix-core instructions included) over its measured duration, set against the issue
+    # rate of one wave64 instruction per 4 clocks per SIMD, 256 CUs x 4 SIMDs x 2.4 GHz / 4.
     roofline_alu = None
     vpath = os.path.join(ROOT, "profiles", "valu.json")
     try:
-        n_valu = json.load(open(vpath)).get(args.workload, {}).get("score_kernel")
+        n_valu = json.load(open(vpath)).get(args.workload, {}).get(score_name)
         if n_valu and score_us:
             peak = 256 * 4 * 2.4e9 / 4 / 1e9
             ach = n_valu / (score_us * 1e-6) / 1e9
-            roofline_alu = {"bound": "alu", "kernel": "score_kernel", "achieved": round(ach, 1), "peak": round(peak, 1),
+            roofline_alu = {"bound": "alu", "kernel": score_name, "achieved": round(ach, 1), "peak": round(peak, 1),
                             "unit": "G wave64 vector instructions/s", "frac": round(ach / peak, 3),
                             "instructions_per_launch": n_valu}
     except Exception:
@@ -223,7 +226,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            roofline["traffic"] = json.load(open(tpath)).get(args.workload, {}).get("score_kernel")
+            roofline["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(score_name)
         except Exception:
             roofline["traffic"] = None
     attend_us = per_kernel_us["attend"]

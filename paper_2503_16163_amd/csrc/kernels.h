@@ -36,6 +36,10 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
 
 // the same for 8 or 16 query rows per KV head, on the matrix cores
 bool score_uses_matrix_cores(int G, int n_rows);
+// one query head per KV head, two rows: integer matrix cores (q must be 16-byte aligned)
+bool score_uses_int8_matrix_cores(int G, int n_rows);
+hipError_t launch_score_i8(const LayerView& L, const void* q, int Nq, float sm_scale, float* logits,
+                           size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
 hipError_t launch_score_mfma(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
                              size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
 

@@ -118,6 +118,33 @@ def test_matrix_core_value_path_keeps_fp32_accuracy(Hq, Hkv, dtype, bits, g):
         c.close()
 
 
+@pytest.mark.parametrize("dtype,bits,g,spread", [(synth.FP16, 2, 32, 1.0), (synth.BF16, 1, 64, 1.0), (synth.FP16, 2, 32, 4096.0),
+                                                  (synth.BF16, 2, 64, 4096.0)])
+def test_integer_matrix_core_scoring_keeps_fp32_accuracy(dtype, bits, g, spread):
+    """One query head per KV head, two rows: scoring runs on the integer matrix cores with the folded multipliers
+    q*s as 32-bit fixed point relative to the largest of their (row, token group).  The logits have to stay as
+    close to the oracle as an fp32 accumulation (a few 1e-7 of the largest logit); a lost byte plane, a wrong
+    byte sign or a scale taken from the wrong group shows as 1e-3 or more.  spread > 1: the key channels get
+    magnitudes from 1 to `spread` (a token group's multipliers then span 12 binary orders), which is where a
+    fixed-point format with too few bits would lose the small channels."""
+    from tests.harness import Case
+    c = Case(1, 3, 3, 2500, dtype, bits, g, 64, seed=4300 + bits * 10 + g, n_outlier=4 if spread == 1.0 else 0)
+    try:
+        if spread > 1.0:
+            scale = np.exp2(np.floor(np.linspace(0.0, np.log2(spread), 128))).astype(np.float32)
+            rng = np.random.default_rng(7)
+            for h in range(3):
+                kf = synth.from_bits(c.k_bits[0, h], dtype) * scale[rng.permutation(128)][None, :]
+                c.k_bits[0, h] = synth.to_bits(kf, dtype)
+        c.load()
+        for t in range(2):
+            c.append_token(t)
+            c.decode_step()
+        assert c.stats["max_logit_err"] < 2e-6, c.stats
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128)])
 def test_long_decode_crosses_flushes(bits, g, R):
     """70 decode steps from a short prompt: the residual ring wraps and groups are flushed during decoding
