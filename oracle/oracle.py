@@ -25,11 +25,15 @@ def lib():
         L.orc_widen.restype = f32
         L.orc_widen.argtypes = [C.c_uint16, i32]
         L.orc_quantize_group.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+        L.orc_quantize_group_form.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
         L.orc_derive_scale_zero.argtypes = [f32, f32, i32, vp, vp]
+        L.orc_derive_scale_zero_form.argtypes = [f32, f32, i32, i32, vp, vp]
         L.orc_pack_group.argtypes = [vp, i32, i32, vp]
         L.orc_unpack_group.argtypes = [vp, i32, i32, vp]
         L.orc_cache_create.restype = vp
         L.orc_cache_create.argtypes = [i32] * 5
+        L.orc_cache_create_form.restype = vp
+        L.orc_cache_create_form.argtypes = [i32] * 6
         L.orc_cache_destroy.restype = None
         L.orc_cache_destroy.argtypes = [vp]
         L.orc_cache_append.argtypes = [vp, vp, vp, i32]
@@ -73,20 +77,23 @@ def widen(bits, dtype):
     return out
 
 
-def quantize_group(x, bits):
+IMPROVED_1BIT, KIVI_1BIT = 0, 1   # Eq. 3, and Eq. 2 with B = 1 (Section 4.4 / Table 5, "original")
+
+
+def quantize_group(x, bits, one_bit_form=IMPROVED_1BIT):
     """Eq. 2 / Eq. 3 on one group.  Returns (codes u8[g], mn, mx, s, z) with float32 scalars."""
     x = np.ascontiguousarray(x, np.float32)
     g = x.size
     codes = np.empty(g, np.uint8)
     out = np.empty(4, np.float32)
-    _check(lib().orc_quantize_group(_p(x), g, bits, _p(out[0:1]), _p(out[1:2]), _p(out[2:3]),
-                                    _p(out[3:4]), _p(codes)), "quantize_group")
+    _check(lib().orc_quantize_group_form(_p(x), g, bits, one_bit_form, _p(out[0:1]), _p(out[1:2]), _p(out[2:3]),
+                                         _p(out[3:4]), _p(codes)), "quantize_group")
     return codes, out[0], out[1], out[2], out[3]
 
 
-def derive_scale_zero(mn, mx, bits):
+def derive_scale_zero(mn, mx, bits, one_bit_form=IMPROVED_1BIT):
     out = np.empty(2, np.float32)
-    _check(lib().orc_derive_scale_zero(float(mn), float(mx), bits, _p(out[0:1]), _p(out[1:2])),
+    _check(lib().orc_derive_scale_zero_form(float(mn), float(mx), bits, one_bit_form, _p(out[0:1]), _p(out[1:2])),
            "derive_scale_zero")
     return out[0], out[1]
 
@@ -108,9 +115,9 @@ def unpack_group(packed, g, bits):
 class Cache:
     """The SpeCache state of one (batch, KV head): 16-bit history C and low-bit copy C'."""
 
-    def __init__(self, D, bits, g, R, dtype):
+    def __init__(self, D, bits, g, R, dtype, one_bit_form=IMPROVED_1BIT):
         self.D, self.bits, self.g, self.R, self.dtype = D, bits, g, R, dtype
-        self._h = lib().orc_cache_create(D, bits, g, R, dtype)
+        self._h = lib().orc_cache_create_form(D, bits, g, R, dtype, one_bit_form)
         if not self._h:
             raise ValueError("oracle cache: invalid configuration")
 

@@ -70,13 +70,15 @@ float widen(uint16_t bits, int dtype) {
 // Given g values X: mn = min X, mx = max X.
 //   B >= 2 (Eq. 2):  z = mn,                 s = (mx - mn) * c_B,  c_B = float(1/(2^B-1))
 //   B == 1 (Eq. 3):  z = (3*mn + mx) * 0.25, s = (mx - mn) * 0.5
+//   B == 1, form 1 (the unmodified 1-bit KIVI of Section 4.4 / Table 5, "original"): Eq. 2 with
+//                    B = 1, i.e. z = mn, s = mx - mn: the two levels are the group's extremes
 //   code = clamp( floor((x - z)/s + 0.5), 0, 2^B-1 ),  all in binary32;
 //   s == 0 (constant group) -> every code 0.
 // Rounding is half-up, which matches Eq. 3's closed lower / open upper
 // interval ends (the exact midpoint belongs to the upper level).
 
-void derive_scale_zero(float mn, float mx, int bits, float* s, float* z) {
-    if (bits == 1) {
+void derive_scale_zero(float mn, float mx, int bits, int one_bit_form, float* s, float* z) {
+    if (bits == 1 && one_bit_form == 0) {
         const float three_mn = 3.0f * mn;
         const float sum = three_mn + mx;
         *z = sum * 0.25f;
@@ -103,7 +105,7 @@ int quantize_one(float x, float s, float z, int bits) {
     return c;
 }
 
-void quantize_group(const float* x, int g, int stride, int bits,
+void quantize_group(const float* x, int g, int stride, int bits, int one_bit_form,
                     float* mn_out, float* mx_out, uint8_t* codes, int code_stride) {
     float mn = x[0], mx = x[0];
     for (int e = 1; e < g; ++e) {
@@ -112,7 +114,7 @@ void quantize_group(const float* x, int g, int stride, int bits,
         if (v > mx) mx = v;
     }
     float s, z;
-    derive_scale_zero(mn, mx, bits, &s, &z);
+    derive_scale_zero(mn, mx, bits, one_bit_form, &s, &z);
     for (int e = 0; e < g; ++e)
         codes[(size_t)e * code_stride] = (uint8_t)quantize_one(x[(size_t)e * stride], s, z, bits);
     *mn_out = mn;
@@ -132,6 +134,7 @@ void quantize_group(const float* x, int g, int stride, int bits,
 
 struct Cache {
     int D, bits, g, R, dtype;
+    int one_bit_form = 0;                    // 0: Eq. 3; 1: Eq. 2 with B = 1 (Table 5 "original")
     int N = 0, Nq = 0;
     std::vector<uint16_t> k_raw, v_raw;      // [N][D] 16-bit patterns as given
     std::vector<float> k_full, v_full;       // [N][D] widened
@@ -150,14 +153,14 @@ void flush_oldest_group(Cache& c) {
     c.v_mx.resize((size_t)(t0 + g) * (D / g));
     // keys: one group per channel, running over the g tokens
     for (int ch = 0; ch < D; ++ch) {
-        quantize_group(&c.k_full[(size_t)t0 * D + ch], g, D, c.bits,
+        quantize_group(&c.k_full[(size_t)t0 * D + ch], g, D, c.bits, c.one_bit_form,
                        &c.k_mn[(size_t)(t0 / g) * D + ch], &c.k_mx[(size_t)(t0 / g) * D + ch],
                        &c.k_code[(size_t)t0 * D + ch], D);
     }
     // values: per token, one group per g consecutive channels
     for (int t = t0; t < t0 + g; ++t) {
         for (int m = 0; m < D / g; ++m) {
-            quantize_group(&c.v_full[(size_t)t * D + m * g], g, 1, c.bits,
+            quantize_group(&c.v_full[(size_t)t * D + m * g], g, 1, c.bits, c.one_bit_form,
                            &c.v_mn[(size_t)t * (D / g) + m], &c.v_mx[(size_t)t * (D / g) + m],
                            &c.v_code[(size_t)t * D + m * g], 1);
         }
@@ -169,14 +172,14 @@ void flush_oldest_group(Cache& c) {
 double deq_k(const Cache& c, int t, int ch) {
     float s, z;
     const size_t gi = (size_t)(t / c.g) * c.D + ch;
-    derive_scale_zero(c.k_mn[gi], c.k_mx[gi], c.bits, &s, &z);
+    derive_scale_zero(c.k_mn[gi], c.k_mx[gi], c.bits, c.one_bit_form, &s, &z);
     return (double)c.k_code[(size_t)t * c.D + ch] * (double)s + (double)z;
 }
 
 double deq_v(const Cache& c, int t, int ch) {
     float s, z;
     const size_t gi = (size_t)t * (c.D / c.g) + ch / c.g;
-    derive_scale_zero(c.v_mn[gi], c.v_mx[gi], c.bits, &s, &z);
+    derive_scale_zero(c.v_mn[gi], c.v_mx[gi], c.bits, c.one_bit_form, &s, &z);
     return (double)c.v_code[(size_t)t * c.D + ch] * (double)s + (double)z;
 }
 
@@ -211,18 +214,28 @@ enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ESTATE = -2 };
 float orc_widen(uint16_t bits, int dtype) { return widen(bits, dtype); }
 
 // Eq. 2 / Eq. 3 on one contiguous group of g floats.
+// one_bit_form: 0 = Eq. 3, 1 = Eq. 2 with B = 1 (only read when bits == 1).
+int orc_quantize_group_form(const float* x, int g, int bits, int one_bit_form, float* mn, float* mx,
+                            float* s, float* z, uint8_t* codes) {
+    if (!x || g <= 0 || bits < 1 || bits > 8 || (one_bit_form != 0 && one_bit_form != 1)) return ORC_EINVAL;
+    quantize_group(x, g, 1, bits, one_bit_form, mn, mx, codes, 1);
+    derive_scale_zero(*mn, *mx, bits, one_bit_form, s, z);
+    return ORC_OK;
+}
+
 int orc_quantize_group(const float* x, int g, int bits, float* mn, float* mx,
                        float* s, float* z, uint8_t* codes) {
-    if (!x || g <= 0 || bits < 1 || bits > 8) return ORC_EINVAL;
-    quantize_group(x, g, 1, bits, mn, mx, codes, 1);
-    derive_scale_zero(*mn, *mx, bits, s, z);
+    return orc_quantize_group_form(x, g, bits, 0, mn, mx, s, z, codes);
+}
+
+int orc_derive_scale_zero_form(float mn, float mx, int bits, int one_bit_form, float* s, float* z) {
+    if (bits < 1 || bits > 8 || (one_bit_form != 0 && one_bit_form != 1)) return ORC_EINVAL;
+    derive_scale_zero(mn, mx, bits, one_bit_form, s, z);
     return ORC_OK;
 }
 
 int orc_derive_scale_zero(float mn, float mx, int bits, float* s, float* z) {
-    if (bits < 1 || bits > 8) return ORC_EINVAL;
-    derive_scale_zero(mn, mx, bits, s, z);
-    return ORC_OK;
+    return orc_derive_scale_zero_form(mn, mx, bits, 0, s, z);
 }
 
 // Canonical bit packing used for the bit-exact comparison of codes: element e
@@ -252,14 +265,18 @@ int orc_unpack_group(const uint8_t* packed, int g, int bits, uint8_t* codes) {
     return ORC_OK;
 }
 
-void* orc_cache_create(int D, int bits, int g, int R, int dtype) {
+void* orc_cache_create_form(int D, int bits, int g, int R, int dtype, int one_bit_form) {
     if (D <= 0 || (bits != 1 && bits != 2 && bits != 4 && bits != 8) || g <= 0 || D % g ||
-        R < g || R % g || (dtype != 0 && dtype != 1))
+        R < g || R % g || (dtype != 0 && dtype != 1) || (one_bit_form != 0 && one_bit_form != 1))
         return nullptr;
     Cache* c = new (std::nothrow) Cache();
     if (!c) return nullptr;
-    c->D = D; c->bits = bits; c->g = g; c->R = R; c->dtype = dtype;
+    c->D = D; c->bits = bits; c->g = g; c->R = R; c->dtype = dtype; c->one_bit_form = one_bit_form;
     return c;
+}
+
+void* orc_cache_create(int D, int bits, int g, int R, int dtype) {
+    return orc_cache_create_form(D, bits, g, R, dtype, 0);
 }
 
 void orc_cache_destroy(void* h) { delete static_cast<Cache*>(h); }
@@ -304,13 +321,13 @@ int orc_cache_export(void* h, uint8_t* k_codes, float* k_mnmx, float* k_sz,
     if (v_codes) std::memcpy(v_codes, c->v_code.data(), (size_t)c->Nq * D);
     for (size_t i = 0; i < (size_t)(c->Nq / g) * D; ++i) {
         float s, z;
-        derive_scale_zero(c->k_mn[i], c->k_mx[i], c->bits, &s, &z);
+        derive_scale_zero(c->k_mn[i], c->k_mx[i], c->bits, c->one_bit_form, &s, &z);
         if (k_mnmx) { k_mnmx[2 * i] = c->k_mn[i]; k_mnmx[2 * i + 1] = c->k_mx[i]; }
         if (k_sz) { k_sz[2 * i] = s; k_sz[2 * i + 1] = z; }
     }
     for (size_t i = 0; i < (size_t)c->Nq * (D / g); ++i) {
         float s, z;
-        derive_scale_zero(c->v_mn[i], c->v_mx[i], c->bits, &s, &z);
+        derive_scale_zero(c->v_mn[i], c->v_mx[i], c->bits, c->one_bit_form, &s, &z);
         if (v_mnmx) { v_mnmx[2 * i] = c->v_mn[i]; v_mnmx[2 * i + 1] = c->v_mx[i]; }
         if (v_sz) { v_sz[2 * i] = s; v_sz[2 * i + 1] = z; }
     }

@@ -70,6 +70,70 @@ def test_eq3_two_levels_only(oracle, dtype):
         assert np.all(codes[x > mid + slack] == 1)
 
 
+def test_plain_one_bit_golden(oracle):
+    """Eq. 2 with B = 1 (Table 5 "original"): the two levels are the group's extremes."""
+    for mn, mx, x, code, level in _rows("eq2_one_bit_plain_levels.txt"):
+        grp = np.full(32, mn, np.float32)
+        grp[1], grp[2] = mx, x
+        codes, gmn, gmx, s, z = oracle.quantize_group(grp, 1, oracle.KIVI_1BIT)
+        assert (gmn, gmx) == (mn, mx)
+        assert float(z) == mn and float(s) == mx - mn
+        assert codes[2] == code, (mn, mx, x)
+        assert codes[0] == 0 and codes[1] == 1
+        assert float(codes[2]) * float(s) + float(z) == level
+
+
+@pytest.mark.parametrize("dtype", [synth.FP16, synth.BF16])
+def test_plain_one_bit_is_nearest_extreme_and_eq3_halves_its_error(oracle, dtype):
+    """Brute force: every value goes to the nearer extreme.  And the reason Eq. 3 exists (Section 3.4,
+    Table 5): its worst error is a quarter of the range, the plain form's is half of it."""
+    rng = np.random.default_rng(5)
+    worst_plain, worst_eq3 = 0.0, 0.0
+    for _ in range(200):
+        x = synth.from_bits(synth.to_bits(rng.normal(size=64) * rng.choice([0.01, 1, 50]), dtype), dtype)
+        codes, mn, mx, s, z = oracle.quantize_group(x, 1, oracle.KIVI_1BIT)
+        rng_x = float(mx) - float(mn)
+        deq = codes.astype(np.float64) * float(s) + float(z)
+        assert set(np.unique(deq)) <= {float(mn), float(mx)}
+        near_hi = np.abs(x - float(mx)) < np.abs(x - float(mn))
+        tie = np.abs(np.abs(x - float(mx)) - np.abs(x - float(mn))) <= 4 * np.spacing(np.float32(abs(rng_x)))
+        assert np.all((codes == 1)[~tie] == near_hi[~tie])
+        err_plain = np.abs(deq - x).max() / rng_x
+        c3, _, _, s3, z3 = oracle.quantize_group(x, 1, oracle.IMPROVED_1BIT)
+        err_eq3 = np.abs(c3.astype(np.float64) * float(s3) + float(z3) - x).max() / rng_x
+        assert err_plain <= 0.5 + 1e-6 and err_eq3 <= 0.25 + 1e-6
+        worst_plain, worst_eq3 = max(worst_plain, err_plain), max(worst_eq3, err_eq3)
+        # both forms cut the group at the same midpoint: identical codes away from it
+        assert np.all(c3[~tie] == codes[~tie])
+    assert worst_plain > 0.4 and worst_eq3 > 0.2          # the bounds are attained on random groups
+
+
+def test_plain_one_bit_cache_keeps_eq3_codes_and_extreme_levels(oracle):
+    """A cache built with the plain form holds the same codes and (min, max) as one built with Eq. 3 (same
+    midpoint) and dequantises to the extremes; its attention output differs."""
+    rng = np.random.default_rng(9)
+    k = synth.to_bits(rng.normal(size=(128, 128)), synth.FP16)
+    v = synth.to_bits(rng.normal(size=(128, 128)), synth.FP16)
+    a = oracle.Cache(128, 1, 32, 64, synth.FP16)
+    b = oracle.Cache(128, 1, 32, 64, synth.FP16, oracle.KIVI_1BIT)
+    a.append(k, v)
+    b.append(k, v)
+    ea, eb = a.export(), b.export()
+    assert ea["k_mnmx"].tobytes() == eb["k_mnmx"].tobytes() and ea["v_mnmx"].tobytes() == eb["v_mnmx"].tobytes()
+    same = (ea["k_codes"] == eb["k_codes"]).mean()
+    assert same > 0.999                                     # only exact-midpoint elements may differ
+    assert np.array_equal(eb["k_sz"][..., 1], eb["k_mnmx"][..., 0])                     # z = min
+    assert np.array_equal(eb["k_sz"][..., 0], eb["k_mnmx"][..., 1] - eb["k_mnmx"][..., 0])   # s = max - min
+    kd, _ = b.dequant()
+    nq = b.counts()[1]
+    mn = np.repeat(eb["k_mnmx"][..., 0], 32, axis=0)[:nq]
+    mx = np.repeat(eb["k_mnmx"][..., 1], 32, axis=0)[:nq]
+    assert np.all((kd == mn) | (kd == mx))
+    q = synth.to_bits(rng.normal(size=(1, 2, 128)), synth.FP16)
+    oa, ob = a.attend(q, 0.088), b.attend(q, 0.088)
+    assert np.abs(oa - ob).max() > 1e-3
+
+
 # ---------------------------------------------------------------- Eq. 2 (P2)
 
 def test_eq2_levels_golden(oracle):
