@@ -46,6 +46,7 @@ typedef enum specache_status {
 } specache_status;
 
 enum { SPECACHE_FP16 = 0, SPECACHE_BF16 = 1 };
+enum { SPECACHE_1BIT_IMPROVED = 0, SPECACHE_1BIT_KIVI = 1 };
 
 /*
  * Configuration (Section 4.1 "Implementation Details" names the knobs: bit width,
@@ -68,6 +69,9 @@ typedef struct specache_config {
     int32_t topk;       /* k: 1 .. 4096                                                */
     int32_t dtype;      /* SPECACHE_FP16 or SPECACHE_BF16: type of K, V, q and C       */
     float sm_scale;     /* logit scale; <= 0 selects 1/sqrt(head_dim)                  */
+    int32_t one_bit_form; /* read when bits == 1: SPECACHE_1BIT_IMPROVED (Eq. 3, the paper's
+                           choice) or SPECACHE_1BIT_KIVI (Eq. 2 with B = 1, the unmodified
+                           quantiser that Section 4.4 / Table 5 compare against)        */
 } specache_config;
 
 typedef struct specache_ctx specache_ctx;

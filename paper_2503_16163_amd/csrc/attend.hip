@@ -325,7 +325,7 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
 #pragma unroll
                 for (int m = 0; m < M; ++m) {
                     float sc, z;
-                    derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), sc, z);
+                    derive_scale_zero<BITS>(widen16<BF16>(meta[tt][m] & 0xFFFFu), widen16<BF16>(meta[tt][m] >> 16), L.one_bit_plain, sc, z);
                     scv[m] = sc;
                     zv[m] = z;
                     if constexpr (kSplit) {

@@ -13,6 +13,7 @@ struct LayerView {
     int G;             // query heads per KV head
     int bits, group, R, max_seq, topk;
     bool bf16;
+    bool one_bit_plain;   // bits == 1: Eq. 2 with B = 1 instead of Eq. 3
     uint8_t* kc;       // K codes   [rows][kc_stride bytes]
     uint32_t* km;      // K meta    [rows][km_stride dwords]  ([group j][128])
     uint8_t* vc;       // V codes   [rows][vc_stride bytes]

@@ -58,12 +58,15 @@ __device__ __forceinline__ float widen16(uint32_t bits16) {
 // ---- Eq. 2 / Eq. 3: scale and zero-point from the stored (min, max) -----------
 // Every step is a single IEEE binary32 operation (no contraction): the integer
 // codes depend on it.
+// plain_one_bit selects, for BITS == 1, the unmodified form (Eq. 2 with B = 1: z = min,
+// s = max - min; the "original" 1-bit KIVI of Section 4.4 / Table 5) instead of Eq. 3.
 template <int BITS>
-__device__ __forceinline__ void derive_scale_zero(float mn, float mx, float& s, float& z) {
+__device__ __forceinline__ void derive_scale_zero(float mn, float mx, bool plain_one_bit, float& s, float& z) {
     const float range = __fsub_rn(mx, mn);
     if constexpr (BITS == 1) {
-        z = __fmul_rn(__fadd_rn(__fmul_rn(3.0f, mn), mx), 0.25f);
-        s = __fmul_rn(range, 0.5f);
+        const float z3 = __fmul_rn(__fadd_rn(__fmul_rn(3.0f, mn), mx), 0.25f);
+        z = plain_one_bit ? mn : z3;
+        s = plain_one_bit ? range : __fmul_rn(range, 0.5f);
     } else {
         constexpr float cB = (float)(1.0 / (double)((1 << BITS) - 1));
         z = mn;

@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
         float ks[4], kz[4], krs[4];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            derive_scale_zero<BITS>(kmin[b], kmax[b], ks[b], kz[b]);
+            derive_scale_zero<BITS>(kmin[b], kmax[b], L.one_bit_plain, ks[b], kz[b]);
             krs[b] = safe_rcp(ks[b]);
         }
         uint32_t kw[NT];
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
         }
         if (j % VL == 0) vm[e * M + j / VL] = narrow16<BF16>(mn) | (narrow16<BF16>(mx) << 16);
         float vs, vz;
-        derive_scale_zero<BITS>(mn, mx, vs, vz);
+        derive_scale_zero<BITS>(mn, mx, L.one_bit_plain, vs, vz);
         const float vrs = safe_rcp(vs);
         bool unsafe = !(vrs == vrs);
         uint32_t byte = 0;
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(128) void export_kernel(LayerView L, int Nq, uint8_
         if (k_mnmx) { k_mnmx[2 * gi] = (uint16_t)(m & 0xFFFFu); k_mnmx[2 * gi + 1] = (uint16_t)(m >> 16); }
         if (k_sz) {
             float s, z;
-            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), s, z);
+            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), L.one_bit_plain, s, z);
             k_sz[2 * gi] = s;
             k_sz[2 * gi + 1] = z;
         }
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(128) void export_kernel(LayerView L, int Nq, uint8_
         if (v_mnmx) { v_mnmx[2 * gi] = (uint16_t)(m & 0xFFFFu); v_mnmx[2 * gi + 1] = (uint16_t)(m >> 16); }
         if (v_sz) {
             float s, z;
-            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), s, z);
+            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), L.one_bit_plain, s, z);
             v_sz[2 * gi] = s;
             v_sz[2 * gi + 1] = z;
         }

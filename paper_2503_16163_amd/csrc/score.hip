@@ -134,7 +134,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
             for (int h = 0; h < HPD; ++h) {
                 const uint32_t m = comp(mt[i][h / 4], h % 4);
                 float sc, z;
-                derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), sc, z);
+                derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), L.one_bit_plain, sc, z);
                 // the codes of mask h arrive scaled by 2^(BITS*h)
                 const float sf = sc * __uint_as_float((uint32_t)(127 - BITS * h) << 23);
                 float qs[RH];

@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(6, 
         for (int b = 0; b < 4; ++b) {
             const uint32_t m = mq ? mt[b].y : mt[b].x;
             float sc, z;
-            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), sc, z);
+            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), L.one_bit_plain, sc, z);
             const int e = 4 * mq + b;
 #pragma unroll
             for (int r = 0; r < 2; ++r) {

@@ -154,8 +154,8 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(LayerView L, co
             const uint32_t* km = L.km + (size_t)row * L.km_stride + (size_t)grp * kD;
             const uint32_t m0 = km[k_meta_index(2 * lane)], m1 = km[k_meta_index(2 * lane + 1)];
             float s0, z0, s1, z1;
-            derive_scale_zero<BITS>(widen16<BF16>(m0 & 0xFFFFu), widen16<BF16>(m0 >> 16), s0, z0);
-            derive_scale_zero<BITS>(widen16<BF16>(m1 & 0xFFFFu), widen16<BF16>(m1 >> 16), s1, z1);
+            derive_scale_zero<BITS>(widen16<BF16>(m0 & 0xFFFFu), widen16<BF16>(m0 >> 16), L.one_bit_plain, s0, z0);
+            derive_scale_zero<BITS>(widen16<BF16>(m1 & 0xFFFFu), widen16<BF16>(m1 >> 16), L.one_bit_plain, s1, z1);
             // the table holds s scaled by a power of two chosen from the group's largest s (s' < 2^8),
             // so that q' s' < 2^15 sits near the top of the f16 range
             const float smax = wave_max_nonneg(fmaxf(s0, s1));

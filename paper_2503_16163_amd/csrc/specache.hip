@@ -172,6 +172,8 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (G != 1 && G != 2 && G != 4 && G != 8) return fail(nullptr, SPECACHE_EINVAL, "n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
     if (c.head_dim != kD) return fail(nullptr, SPECACHE_EINVAL, "head_dim must be 128");
     if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
+    if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
+        return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
     if (c.group != 32 && c.group != 64) return fail(nullptr, SPECACHE_EINVAL, "group must be 32 or 64");
     if (c.residual < c.group || c.residual % c.group || c.residual > 256)
         return fail(nullptr, SPECACHE_EINVAL, "residual must be a multiple of group in [group, 256]");
@@ -219,6 +221,7 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     for (Layer& L : ctx->layers) {
         LayerView& v = L.view;
         v.rows = rows; v.G = G; v.bits = c.bits; v.group = c.group; v.R = c.residual;
+        v.one_bit_plain = c.bits == 1 && c.one_bit_form == SPECACHE_1BIT_KIVI;
         v.max_seq = c.max_seq; v.topk = c.topk; v.bf16 = c.dtype == SPECACHE_BF16;
         v.kc_stride = (cap + kTileTokens - 1) / kTileTokens * k_tile_bytes(c.bits);
         v.vc_stride = cap / kBlockTokens * code_block_bytes(c.bits);

@@ -63,13 +63,14 @@ class Case:
     """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
-                 max_seq=None, n_outlier=4):
+                 max_seq=None, n_outlier=4, one_bit_form=0):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
         self.sample = sample if sample is not None else [(b, h) for b in range(B) for h in range(Hkv)]
         cap = max_seq or ((S + 64 + 63) // 64) * 64
-        self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R)
+        self.one_bit_form = one_bit_form
+        self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form)
         self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
         self.oc = {}
         self.step_k, self.step_v = [], []
@@ -94,7 +95,7 @@ class Case:
                 self.sc.quantize_append(0, kd, vd, b - a)
         torch.cuda.synchronize()
         for (b, h) in self.sample:
-            c = orc.Cache(self.D, self.bits, self.g, self.R, self.dtype)
+            c = orc.Cache(self.D, self.bits, self.g, self.R, self.dtype, self.one_bit_form)
             c.append(self.k_bits[b, h], self.v_bits[b, h])
             self.oc[(b, h)] = c
 

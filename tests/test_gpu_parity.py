@@ -234,6 +234,26 @@ def test_slot_reuse_orders_gather_after_attend():
         c.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,g", [(2, 2, synth.FP16, 32), (4, 2, synth.BF16, 64), (8, 1, synth.BF16, 32)])
+def test_unmodified_one_bit_kivi(Hq, Hkv, dtype, g):
+    """one_bit_form = SPECACHE_1BIT_KIVI: Eq. 2 with B = 1 (Section 4.4 / Table 5, "original").  Codes, stored
+    extremes and derived (s, z) bit-exact, scores, selection and attention against the oracle's same form; the
+    three shapes take the three scoring kernels."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 1300, dtype, 1, g, 48, seed=2600 + g, one_bit_form=1)
+    try:
+        c.load()
+        c.check_quantized()
+        for t in range(3):
+            c.decode_step()
+            c.append_token(t)
+        c.check_quantized()
+    finally:
+        c.close()
+    with pytest.raises(binding.SpeCacheError):
+        binding.SpeCache(1, 1, 1, 1, 1, 32, 256, 8, synth.FP16, one_bit_form=2)
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
