@@ -42,6 +42,7 @@ def lib():
         L.orc_cache_dequant.argtypes = [vp, vp, vp]
         L.orc_cache_history.argtypes = [vp, vp, vp]
         L.orc_scores.argtypes = [vp, vp, i32, i32, f64, vp, vp]
+        L.orc_scores_form.argtypes = [vp, vp, i32, i32, f64, i32, vp, vp]
         L.orc_topk.argtypes = [vp, i32, i32, vp]
         L.orc_attend.argtypes = [vp, vp, i32, i32, f64, vp, i32, vp, vp, vp]
         L.orc_full_attention.argtypes = [vp, vp, i32, i32, f64, vp, vp, vp, vp]
@@ -77,6 +78,7 @@ def widen(bits, dtype):
     return out
 
 
+SELECT_MAX_LOGIT, SELECT_MAX_LOGPROB = 0, 1   # how the query heads of a KV head share one index set
 IMPROVED_1BIT, KIVI_1BIT = 0, 1   # Eq. 3, and Eq. 2 with B = 1 (Section 4.4 / Table 5, "original")
 
 
@@ -159,14 +161,16 @@ class Cache:
         _check(lib().orc_cache_history(self._h, _p(k), _p(v)), "history")
         return k, v
 
-    def scores(self, q, sm_scale):
-        """q: uint16 [G, rows, D].  Returns (logits f64 [G, rows, Nq], sigma f64 [Nq])."""
+    def scores(self, q, sm_scale, select_form=0):
+        """q: uint16 [G, rows, D].  Returns (logits f64 [G, rows, Nq], sigma f64 [Nq]).
+        select_form: SELECT_MAX_LOGIT (0) or SELECT_MAX_LOGPROB (1)."""
         q = _u16(q)
         G, rows, D = q.shape
         assert D == self.D
         _, nq = self.counts()
         logits, sigma = np.empty((G, rows, nq)), np.empty(nq)
-        _check(lib().orc_scores(self._h, _p(q), G, rows, float(sm_scale), _p(logits), _p(sigma)), "scores")
+        _check(lib().orc_scores_form(self._h, _p(q), G, rows, float(sm_scale), select_form, _p(logits), _p(sigma)),
+               "scores")
         return logits, sigma
 
     def attend(self, q, sm_scale, P=None, k_spec=None, v_spec=None):

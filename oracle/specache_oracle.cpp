@@ -359,16 +359,22 @@ int orc_cache_history(void* h, double* k, double* v) {
 
 // Low-bit logits (Appendix A "Decoding": Q K^T on the low-bit copy):
 //   logits[h][row][i] = sm_scale * sum_c q[h][row][c] * K'[i][c],  i < Nq
-// and the selection score of position i for this KV head,
-//   sigma[i] = max over the G query heads of logits[h][rows-1][i].
+// and the selection score of position i for this KV head (the paper is silent on how the G
+// query heads of a KV head share one index set),
+//   select_form 0:  sigma[i] = max over the G query heads of logits[h][rows-1][i];
+//   select_form 1:  sigma[i] = max over the G query heads of the log-probability
+//                   logits[h][rows-1][i] - log sum_{j < Nq} exp(logits[h][rows-1][j]),
+//                   i.e. of the head's softmax over the low-bit positions (ArgTopK is applied to
+//                   the softmax output A in Appendix A; per head the two orders agree, across
+//                   heads this form weighs every head's distribution alike).
 // q: [G][rows][D] 16-bit patterns.
-int orc_scores(void* hc, const uint16_t* q, int G, int rows, double sm_scale,
-               double* logits, double* sigma) {
+int orc_scores_form(void* hc, const uint16_t* q, int G, int rows, double sm_scale, int select_form,
+                    double* logits, double* sigma) {
     Cache* c = static_cast<Cache*>(hc);
-    if (!c || !q || G <= 0 || rows <= 0) return ORC_EINVAL;
+    if (!c || !q || G <= 0 || rows <= 0 || (select_form != 0 && select_form != 1)) return ORC_EINVAL;
     const int D = c->D, Nq = c->Nq;
-    for (int i = 0; i < Nq; ++i) {
-        double best = -std::numeric_limits<double>::infinity();
+    std::vector<double> last((size_t)G * Nq);          // logits of the last row of every head
+    for (int i = 0; i < Nq; ++i)
         for (int h = 0; h < G; ++h)
             for (int r = 0; r < rows; ++r) {
                 double acc = 0.0;
@@ -376,11 +382,28 @@ int orc_scores(void* hc, const uint16_t* q, int G, int rows, double sm_scale,
                     acc += (double)widen(q[((size_t)h * rows + r) * D + ch], c->dtype) * deq_k(*c, i, ch);
                 const double l = sm_scale * acc;
                 if (logits) logits[((size_t)h * rows + r) * Nq + i] = l;
-                if (r == rows - 1) best = std::max(best, l);
+                if (r == rows - 1) last[(size_t)h * Nq + i] = l;
             }
-        if (sigma) sigma[i] = best;
+    if (!sigma) return ORC_OK;
+    std::vector<double> lse(G, 0.0);
+    if (select_form == 1)
+        for (int h = 0; h < G; ++h) {
+            double m = -std::numeric_limits<double>::infinity(), sum = 0.0;
+            for (int i = 0; i < Nq; ++i) m = std::max(m, last[(size_t)h * Nq + i]);
+            for (int i = 0; i < Nq; ++i) sum += std::exp(last[(size_t)h * Nq + i] - m);
+            lse[h] = m + std::log(sum);
+        }
+    for (int i = 0; i < Nq; ++i) {
+        double best = -std::numeric_limits<double>::infinity();
+        for (int h = 0; h < G; ++h) best = std::max(best, last[(size_t)h * Nq + i] - lse[h]);
+        sigma[i] = best;
     }
     return ORC_OK;
+}
+
+int orc_scores(void* hc, const uint16_t* q, int G, int rows, double sm_scale,
+               double* logits, double* sigma) {
+    return orc_scores_form(hc, q, G, rows, sm_scale, 0, logits, sigma);
 }
 
 // ArgTopK: the min(k, n) positions with the largest score, ties to the lower

@@ -329,6 +329,37 @@ def test_scores_are_scaled_q_dot_dequantised_keys(oracle, G):
     assert np.allclose(sigma, want[:, -1, :].max(axis=0), rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("G", [1, 2, 4])
+def test_log_probability_selection_score(oracle, G):
+    """select_form 1: max over heads of the head's log-softmax over the low-bit positions (scipy as the
+    library routine).  With one head it orders the positions as the logits do; with several it differs
+    from the max of raw logits exactly when a head's logits are larger across the board."""
+    from scipy.special import log_softmax
+    c, q, _, _ = _setup(oracle, G=G, dtype=synth.FP16)
+    sm = 0.09
+    logits, sigma = c.scores(q, sm, oracle.SELECT_MAX_LOGPROB)
+    _, sigma_logit = c.scores(q, sm, oracle.SELECT_MAX_LOGIT)
+    want = log_softmax(logits[:, -1, :], axis=-1).max(axis=0)
+    assert np.allclose(sigma, want, rtol=1e-12, atol=1e-12)
+    assert np.all(sigma <= 0) and abs(np.exp(log_softmax(logits[0, -1])).sum() - 1) < 1e-12
+    k = 16
+    if G == 1:
+        assert np.array_equal(oracle.topk(sigma, k), oracle.topk(sigma_logit, k))
+    else:
+        # scale head 0's query up: its raw logits dominate the max-of-logits score everywhere ...
+        qf = synth.from_bits(q, synth.FP16).copy()
+        qf[0] *= 8.0
+        q8 = synth.to_bits(qf, synth.FP16)
+        l8, s_logit = c.scores(q8, sm, oracle.SELECT_MAX_LOGIT)
+        _, s_prob = c.scores(q8, sm, oracle.SELECT_MAX_LOGPROB)
+        top_logit, top_prob = oracle.topk(s_logit, k), oracle.topk(s_prob, k)
+        assert np.array_equal(top_logit, oracle.topk(l8[0, -1], k))       # ... so head 0 alone decides
+        others = set(np.concatenate([oracle.topk(l8[h, -1], k) for h in range(1, G)]).tolist())
+        assert not set(top_logit.tolist()) & others or len(set(top_logit.tolist()) & others) < k
+        assert np.array_equal(np.sort(top_prob), top_prob) and len(set(top_prob.tolist())) == k
+        assert np.allclose(s_prob, log_softmax(l8[:, -1, :], axis=-1).max(axis=0), rtol=1e-12, atol=1e-12)
+
+
 @pytest.mark.parametrize("bits,g,G", [(2, 32, 1), (1, 32, 4), (2, 64, 2)])
 def test_all_positions_prefetched_is_textbook_attention(oracle, bits, g, G):
     """Eq. 1 with K = every quantised position: all low-bit pairs are replaced, so the result
