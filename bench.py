@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (3x), the known-size kernel the FETCH_SIZE/WRITE_SIZE "
                          "counters are scaled by")
+    ap.add_argument("--select", default="logit", choices=["logit", "logprob"],
+                    help="how the query heads of a KV head share one index set: largest logit (default) or largest "
+                         "log-probability over the heads (two more small kernels per layer-step)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -116,7 +119,8 @@ def main():
     sc = None
     while sc is None:
         try:
-            sc = binding.SpeCache(layers, B, Hq, Hkv, bits, g, max_seq, k, dtype, residual=R)
+            sc = binding.SpeCache(layers, B, Hq, Hkv, bits, g, max_seq, k, dtype, residual=R,
+                                  select_form=1 if args.select == "logprob" else 0)
         except binding.SpeCacheError as e:
             if e.code != binding.ENOMEM or layers == 1:
                 raise

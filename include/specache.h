@@ -47,6 +47,7 @@ typedef enum specache_status {
 
 enum { SPECACHE_FP16 = 0, SPECACHE_BF16 = 1 };
 enum { SPECACHE_1BIT_IMPROVED = 0, SPECACHE_1BIT_KIVI = 1 };
+enum { SPECACHE_SELECT_MAX_LOGIT = 0, SPECACHE_SELECT_MAX_LOGPROB = 1 };
 
 /*
  * Configuration (Section 4.1 "Implementation Details" names the knobs: bit width,
@@ -72,6 +73,13 @@ typedef struct specache_config {
     int32_t one_bit_form; /* read when bits == 1: SPECACHE_1BIT_IMPROVED (Eq. 3, the paper's
                            choice) or SPECACHE_1BIT_KIVI (Eq. 2 with B = 1, the unmodified
                            quantiser that Section 4.4 / Table 5 compare against)        */
+    int32_t select_form; /* how the Hq / Hkv query heads of a KV head share one index set (the
+                           paper is silent): SPECACHE_SELECT_MAX_LOGIT, the largest scaled
+                           low-bit logit of the speculative row over the heads, or
+                           SPECACHE_SELECT_MAX_LOGPROB, the largest log-probability, each
+                           head's logits less their log-sum-exp over the low-bit positions
+                           (Appendix A applies ArgTopK to the softmax output).  The same
+                           order when Hq == Hkv                                         */
 } specache_config;
 
 typedef struct specache_ctx specache_ctx;

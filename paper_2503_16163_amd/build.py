@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecache.so")
-SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "topk.hip", "gather.hip", "attend.hip"]
+SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "select.hip", "topk.hip", "gather.hip", "attend.hip"]
 # -ffp-contract=off: the quantiser's binary32 operation order is part of its definition and
 # fused multiply-adds are written out where they are wanted.  Packed FP32 code generation is
 # switched off for the device pass.

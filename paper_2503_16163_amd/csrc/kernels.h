@@ -36,6 +36,11 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream);
 
 // the same for 8 or 16 query rows per KV head, on the matrix cores
+// selection keys from the heads' log-probabilities (after launch_score); scratch of
+// select_logprob_scratch_floats(rows, G, max_seq) floats
+size_t select_logprob_scratch_floats(int rows, int G, int max_seq);
+hipError_t launch_select_logprob(const LayerView& L, int n_rows, int Nq, const float* logits, size_t logit_stride,
+                                 float* scratch, uint32_t* keys, size_t key_stride, hipStream_t stream);
 bool score_uses_matrix_cores(int G, int n_rows);
 // one query head per KV head, two rows: integer matrix cores (q must be 16-byte aligned)
 bool score_uses_int8_matrix_cores(int G, int n_rows);

@@ -56,6 +56,7 @@ struct specache_ctx {
     std::vector<Layer> layers;
     float* logits = nullptr;     // [rows*G*2][logit_stride]
     uint32_t* keys = nullptr;    // [rows][logit_stride]
+    float* lse = nullptr;        // (max, sum) per slice of every head's speculative row (log-probability selection)
     size_t logit_stride = 0;
     AttendScratch scratch{};
     TopkScratch topk_scratch{};
@@ -141,6 +142,7 @@ void free_all(specache_ctx* ctx) {
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     (void)hipFree(ctx->logits);
     (void)hipFree(ctx->keys);
+    (void)hipFree(ctx->lse);
     (void)hipFree(ctx->scratch.part_o);
     (void)hipFree(ctx->scratch.part_ml);
     (void)hipFree(ctx->topk_scratch.cand_keys);
@@ -174,6 +176,8 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
     if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
         return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
+    if (c.select_form != SPECACHE_SELECT_MAX_LOGIT && c.select_form != SPECACHE_SELECT_MAX_LOGPROB)
+        return fail(nullptr, SPECACHE_EINVAL, "select_form must be SPECACHE_SELECT_MAX_LOGIT or SPECACHE_SELECT_MAX_LOGPROB");
     if (c.group != 32 && c.group != 64) return fail(nullptr, SPECACHE_EINVAL, "group must be 32 or 64");
     if (c.residual < c.group || c.residual % c.group || c.residual > 256)
         return fail(nullptr, SPECACHE_EINVAL, "residual must be a multiple of group in [group, 256]");
@@ -248,6 +252,7 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     ctx->logit_stride = cap;
     SPC_ALLOC(hipMalloc((void**)&ctx->logits, (size_t)rows * G * 2 * cap * 4));
     SPC_ALLOC(hipMalloc((void**)&ctx->keys, (size_t)rows * cap * 4));
+    SPC_ALLOC(hipMalloc((void**)&ctx->lse, select_logprob_scratch_floats(rows, G, cap) * 4));
     int max_main = 0;
     for (int n = 1; n <= 2; ++n) {
         const int ch = attend_main_chunk_tokens(G * n);
@@ -327,6 +332,11 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE);
         SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
                                   ctx->logit_stride, st));
+        // several query heads per KV head and the log-probability form: the keys are rewritten from
+        // the logits shifted by every head's log-sum-exp (one head: same order, nothing to do)
+        if (ctx->cfg.select_form == SPECACHE_SELECT_MAX_LOGPROB && L.view.G > 1)
+            SPC_HIP(ctx, launch_select_logprob(L.view, n_rows, L.Nq, ctx->logits, ctx->logit_stride, ctx->lse, ctx->keys,
+                                               ctx->logit_stride, st));
     }
     {
         TimedLaunch t(ctx, st, SPECACHE_K_TOPK);

@@ -63,14 +63,15 @@ class Case:
     """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
-                 max_seq=None, n_outlier=4, one_bit_form=0):
+                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
         self.sample = sample if sample is not None else [(b, h) for b in range(B) for h in range(Hkv)]
         cap = max_seq or ((S + 64 + 63) // 64) * 64
-        self.one_bit_form = one_bit_form
-        self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form)
+        self.one_bit_form, self.select_form = one_bit_form, select_form
+        self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
+                                   select_form=select_form)
         self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
         self.oc = {}
         self.step_k, self.step_v = [], []
@@ -78,6 +79,7 @@ class Case:
         self.idx = [torch.full((B, Hkv, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)]
         self.step_no = 0
         self.stats = dict(band_diffs=0, max_out_err=0.0, max_logit_err=0.0)
+        self.q_head_scale = None     # optional [Hq] factors applied to the synthetic queries of decode_step
 
     def close(self):
         torch.cuda.synchronize()
@@ -139,6 +141,9 @@ class Case:
         t = self.step_no
         nr = self.n_rows
         q_bits = synth.make_queries(self.seed, self.B, self.Hq, self.D, self.dtype, n_rows=nr, sub=t)
+        if self.q_head_scale is not None:
+            scaled = synth.from_bits(q_bits, self.dtype) * np.asarray(self.q_head_scale, np.float32)[None, :, None, None]
+            q_bits = synth.to_bits(scaled, self.dtype).reshape(q_bits.shape)
         ks_bits, vs_bits = synth.make_spec_kv(self.seed, self.B, self.Hkv, self.D, self.dtype, sub=t)
         q = to_dev(q_bits, self.dtype)
         ks, vs = (to_dev(ks_bits, self.dtype), to_dev(vs_bits, self.dtype)) if use_spec else (None, None)
@@ -159,7 +164,7 @@ class Case:
         for (b, h) in self.sample:
             c = self.oc[(b, h)]
             qh = q_bits[b, h * self.G:(h + 1) * self.G]                      # [G, rows, D]
-            ref_logits, sigma = c.scores(qh, self.sm_scale)
+            ref_logits, sigma = c.scores(qh, self.sm_scale, self.select_form)
             if check_logits and nq:
                 got = logits_h[b, h * self.G:(h + 1) * self.G]
                 err = np.abs(got - ref_logits).max() / max(np.abs(ref_logits).max(), 1.0)
@@ -172,6 +177,7 @@ class Case:
             e = check_out(out_h[b, h * self.G:(h + 1) * self.G], ref_out, what=f"attend {(b, h)} step {t}")
             self.stats["max_out_err"] = max(self.stats["max_out_err"], e)
         self.prev_idx = idx_h
+        self.last_q_bits = q_bits
         self.step_no += 1
         return idx_h, out_h
 
@@ -193,7 +199,7 @@ class Case:
         for (b, h) in self.sample:
             c = self.oc[(b, h)]
             qh = q_bits[b, h * self.G:(h + 1) * self.G]
-            _, sigma = c.scores(qh, self.sm_scale)
+            _, sigma = c.scores(qh, self.sm_scale, self.select_form)
             self.stats["band_diffs"] += check_topk(sigma, idx_h[b, h], self.k, what=f"non-spec top-k {(b, h)}")
             ref_out = c.attend(qh, self.sm_scale, P=idx_h[b, h])
             e = check_out(out_h[b, h * self.G:(h + 1) * self.G], ref_out, what=f"non-spec attend {(b, h)}")

@@ -254,6 +254,33 @@ def test_unmodified_one_bit_kivi(Hq, Hkv, dtype, g):
         binding.SpeCache(1, 1, 1, 1, 1, 32, 256, 8, synth.FP16, one_bit_form=2)
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g,n_rows", [(4, 2, synth.FP16, 2, 32, 2), (8, 2, synth.BF16, 1, 32, 2), (8, 1, synth.BF16, 2, 64, 2),
+                                                         (4, 1, synth.FP16, 2, 32, 1), (2, 2, synth.FP16, 2, 32, 2)])
+def test_log_probability_selection(Hq, Hkv, dtype, bits, g, n_rows):
+    """select_form = SPECACHE_SELECT_MAX_LOGPROB: the heads of a KV head are compared by their log-probabilities over
+    the low-bit positions (the oracle's same form decides what has to be selected)."""
+    from tests.harness import Case
+    from oracle import oracle as orc
+    c = Case(1, Hq, Hkv, 2100, dtype, bits, g, 40, seed=2700 + Hq + g, n_rows=n_rows, select_form=1)
+    G = Hq // Hkv
+    if G > 1:      # the first head of every KV head asks four times as loudly: the two forms then disagree
+        c.q_head_scale = [4.0 if h % G == 0 else 1.0 for h in range(Hq)]
+    try:
+        c.load()
+        for t in range(3):
+            c.decode_step(use_spec=n_rows == 2, do_gather=n_rows == 2)
+            c.append_token(t)
+        if G > 1:  # the check above has teeth: on these inputs the max-of-logits form selects another set
+            qh = c.last_q_bits[0, :G]
+            _, s_logit = c.oc[(0, 0)].scores(qh, c.sm_scale, orc.SELECT_MAX_LOGIT)
+            _, s_prob = c.oc[(0, 0)].scores(qh, c.sm_scale, orc.SELECT_MAX_LOGPROB)
+            assert len(set(orc.topk(s_logit, 40).tolist()) & set(orc.topk(s_prob, 40).tolist())) < 30
+    finally:
+        c.close()
+    with pytest.raises(binding.SpeCacheError):
+        binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_form=3)
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
