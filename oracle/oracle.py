@@ -43,6 +43,7 @@ def lib():
         L.orc_cache_history.argtypes = [vp, vp, vp]
         L.orc_scores.argtypes = [vp, vp, i32, i32, f64, vp, vp]
         L.orc_scores_form.argtypes = [vp, vp, i32, i32, f64, i32, vp, vp]
+        L.orc_scores_mixed.argtypes = [vp, vp, i32, i32, f64, i32, vp, i32, vp, vp]
         L.orc_topk.argtypes = [vp, i32, i32, vp]
         L.orc_attend.argtypes = [vp, vp, i32, i32, f64, vp, i32, vp, vp, vp]
         L.orc_full_attention.argtypes = [vp, vp, i32, i32, f64, vp, vp, vp, vp]
@@ -161,16 +162,18 @@ class Cache:
         _check(lib().orc_cache_history(self._h, _p(k), _p(v)), "history")
         return k, v
 
-    def scores(self, q, sm_scale, select_form=0):
+    def scores(self, q, sm_scale, select_form=0, P=None):
         """q: uint16 [G, rows, D].  Returns (logits f64 [G, rows, Nq], sigma f64 [Nq]).
-        select_form: SELECT_MAX_LOGIT (0) or SELECT_MAX_LOGPROB (1)."""
+        select_form: SELECT_MAX_LOGIT (0) or SELECT_MAX_LOGPROB (1).  P: staged positions (int32, -1 ignored):
+        with it the logits are those of the mixed cache (16-bit keys at P), without it pure low-bit."""
         q = _u16(q)
         G, rows, D = q.shape
         assert D == self.D
         _, nq = self.counts()
         logits, sigma = np.empty((G, rows, nq)), np.empty(nq)
-        _check(lib().orc_scores_form(self._h, _p(q), G, rows, float(sm_scale), select_form, _p(logits), _p(sigma)),
-               "scores")
+        P = np.ascontiguousarray(P, np.int32) if P is not None else np.empty(0, np.int32)
+        _check(lib().orc_scores_mixed(self._h, _p(q), G, rows, float(sm_scale), select_form, _p(P) if P.size else None,
+                                      int(P.size), _p(logits), _p(sigma)), "scores")
         return logits, sigma
 
     def attend(self, q, sm_scale, P=None, k_spec=None, v_spec=None):

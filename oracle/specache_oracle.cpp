@@ -368,18 +368,30 @@ int orc_cache_history(void* h, double* k, double* v) {
 //                   the softmax output A in Appendix A; per head the two orders agree, across
 //                   heads this form weighs every head's distribution alike).
 // q: [G][rows][D] 16-bit patterns.
-int orc_scores_form(void* hc, const uint16_t* q, int G, int rows, double sm_scale, int select_form,
-                    double* logits, double* sigma) {
+// P (may be null): positions whose 16-bit pairs are staged; with it the logits are those of the
+// mixed cache C' u C_K of Eq. 1 (Appendix A "Decoding" computes one A on the mixed cache and takes
+// ArgTopK of its second row), i.e. position i in P is scored with its 16-bit key.  Without it they
+// are the pure low-bit logits.  Entries < 0 are ignored.
+int orc_scores_mixed(void* hc, const uint16_t* q, int G, int rows, double sm_scale, int select_form,
+                     const int32_t* P, int nP, double* logits, double* sigma) {
     Cache* c = static_cast<Cache*>(hc);
-    if (!c || !q || G <= 0 || rows <= 0 || (select_form != 0 && select_form != 1)) return ORC_EINVAL;
+    if (!c || !q || G <= 0 || rows <= 0 || (select_form != 0 && select_form != 1) || nP < 0 || (nP > 0 && !P))
+        return ORC_EINVAL;
     const int D = c->D, Nq = c->Nq;
+    std::vector<char> in_p(Nq, 0);
+    for (int j = 0; j < nP; ++j) {
+        if (P[j] < 0) continue;
+        if (P[j] >= Nq) return ORC_ESTATE;
+        in_p[P[j]] = 1;
+    }
     std::vector<double> last((size_t)G * Nq);          // logits of the last row of every head
     for (int i = 0; i < Nq; ++i)
         for (int h = 0; h < G; ++h)
             for (int r = 0; r < rows; ++r) {
                 double acc = 0.0;
                 for (int ch = 0; ch < D; ++ch)
-                    acc += (double)widen(q[((size_t)h * rows + r) * D + ch], c->dtype) * deq_k(*c, i, ch);
+                    acc += (double)widen(q[((size_t)h * rows + r) * D + ch], c->dtype) *
+                           (in_p[i] ? (double)c->k_full[(size_t)i * D + ch] : deq_k(*c, i, ch));
                 const double l = sm_scale * acc;
                 if (logits) logits[((size_t)h * rows + r) * Nq + i] = l;
                 if (r == rows - 1) last[(size_t)h * Nq + i] = l;
@@ -401,9 +413,14 @@ int orc_scores_form(void* hc, const uint16_t* q, int G, int rows, double sm_scal
     return ORC_OK;
 }
 
+int orc_scores_form(void* hc, const uint16_t* q, int G, int rows, double sm_scale, int select_form,
+                    double* logits, double* sigma) {
+    return orc_scores_mixed(hc, q, G, rows, sm_scale, select_form, nullptr, 0, logits, sigma);
+}
+
 int orc_scores(void* hc, const uint16_t* q, int G, int rows, double sm_scale,
                double* logits, double* sigma) {
-    return orc_scores_form(hc, q, G, rows, sm_scale, 0, logits, sigma);
+    return orc_scores_mixed(hc, q, G, rows, sm_scale, 0, nullptr, 0, logits, sigma);
 }
 
 // ArgTopK: the min(k, n) positions with the largest score, ties to the lower

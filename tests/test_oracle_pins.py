@@ -329,6 +329,34 @@ def test_scores_are_scaled_q_dot_dequantised_keys(oracle, G):
     assert np.allclose(sigma, want[:, -1, :].max(axis=0), rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("G", [1, 4])
+def test_scores_on_the_mixed_cache(oracle, G):
+    """Scores with a staged set P: 16-bit keys at P, low-bit keys elsewhere (numpy einsum on both); P empty
+    is the pure low-bit score, P = everything the exact score on the 16-bit history."""
+    c, q, _, _ = _setup(oracle, G=G, dtype=synth.FP16)
+    sm = 0.07
+    nq = c.counts()[1]
+    kd, _ = c.dequant()
+    kh, _ = c.history()
+    qf = synth.from_bits(q, synth.FP16).astype(np.float64)
+    low = sm * np.einsum("grc,nc->grn", qf, kd)
+    exact = sm * np.einsum("grc,nc->grn", qf, kh[:nq])
+    P = np.array([3, -1, 17, nq - 1, 40], np.int32)
+    logits, sigma = c.scores(q, sm, P=P)
+    want = low.copy()
+    want[:, :, P[P >= 0]] = exact[:, :, P[P >= 0]]
+    assert np.allclose(logits, want, rtol=1e-12, atol=1e-12)
+    assert np.allclose(sigma, want[:, -1, :].max(axis=0), rtol=1e-12, atol=1e-12)
+    assert np.abs(low - exact).max() > 1e-3                       # the two caches do differ
+    l0, s0 = c.scores(q, sm, P=np.empty(0, np.int32))
+    l1, _ = c.scores(q, sm)
+    assert np.array_equal(l0, l1)
+    lall, _ = c.scores(q, sm, P=np.arange(nq, dtype=np.int32))
+    assert np.allclose(lall, exact, rtol=1e-12, atol=1e-12)
+    with pytest.raises(RuntimeError):
+        c.scores(q, sm, P=np.array([nq], np.int32))
+
+
 @pytest.mark.parametrize("G", [1, 2, 4])
 def test_log_probability_selection_score(oracle, G):
     """select_form 1: max over heads of the head's log-softmax over the low-bit positions (scipy as the
