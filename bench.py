@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--select", default="logit", choices=["logit", "logprob"],
                     help="how the query heads of a KV head share one index set: largest logit (default) or largest "
                          "log-probability over the heads (two more small kernels per layer-step)")
+    ap.add_argument("--select-cache", default="lowbit", choices=["lowbit", "mixed"],
+                    help="which logits ArgTopK ranks: pure low-bit (default) or the mixed cache's (the staged positions "
+                         "are scored with their 16-bit keys: one more small kernel per layer-step)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -120,7 +123,8 @@ def main():
     while sc is None:
         try:
             sc = binding.SpeCache(layers, B, Hq, Hkv, bits, g, max_seq, k, dtype, residual=R,
-                                  select_form=1 if args.select == "logprob" else 0)
+                                  select_form=1 if args.select == "logprob" else 0,
+                                  select_cache=1 if args.select_cache == "mixed" else 0)
         except binding.SpeCacheError as e:
             if e.code != binding.ENOMEM or layers == 1:
                 raise

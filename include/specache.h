@@ -48,6 +48,7 @@ typedef enum specache_status {
 enum { SPECACHE_FP16 = 0, SPECACHE_BF16 = 1 };
 enum { SPECACHE_1BIT_IMPROVED = 0, SPECACHE_1BIT_KIVI = 1 };
 enum { SPECACHE_SELECT_MAX_LOGIT = 0, SPECACHE_SELECT_MAX_LOGPROB = 1 };
+enum { SPECACHE_SELECT_LOWBIT = 0, SPECACHE_SELECT_MIXED = 1 };
 
 /*
  * Configuration (Section 4.1 "Implementation Details" names the knobs: bit width,
@@ -80,6 +81,11 @@ typedef struct specache_config {
                            head's logits less their log-sum-exp over the low-bit positions
                            (Appendix A applies ArgTopK to the softmax output).  The same
                            order when Hq == Hkv                                         */
+    int32_t select_cache; /* which logits ArgTopK ranks: SPECACHE_SELECT_LOWBIT, the pure
+                           low-bit logits (the "low-bit copy" of Section 1), or
+                           SPECACHE_SELECT_MIXED, those of the mixed cache of Eq. 1: the
+                           positions staged by the layer's last specache_gather are scored
+                           with their 16-bit keys (Appendix A "Decoding" computes one A)  */
 } specache_config;
 
 typedef struct specache_ctx specache_ctx;

@@ -41,6 +41,10 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
 size_t select_logprob_scratch_floats(int rows, int G, int max_seq);
 hipError_t launch_select_logprob(const LayerView& L, int n_rows, int Nq, const float* logits, size_t logit_stride,
                                  float* scratch, uint32_t* keys, size_t key_stride, hipStream_t stream);
+// after launch_score: logits and keys of the staged positions from their 16-bit keys (selection on the mixed cache)
+hipError_t launch_patch_staged(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, const uint16_t* slot,
+                               const int32_t* slot_idx, float* logits, size_t logit_stride, uint32_t* keys,
+                               size_t key_stride, hipStream_t stream);
 bool score_uses_matrix_cores(int G, int n_rows);
 // one query head per KV head, two rows: integer matrix cores (q must be 16-byte aligned)
 bool score_uses_int8_matrix_cores(int G, int n_rows);

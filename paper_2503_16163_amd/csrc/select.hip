@@ -91,7 +91,47 @@ __global__ __launch_bounds__(256) void logprob_keys_kernel(const float* __restri
         make_uint4(float_to_key(best[0]), float_to_key(best[1]), float_to_key(best[2]), float_to_key(best[3]));
 }
 
+// Selection on the mixed cache (Eq. 1; Appendix A "Decoding" computes one A on C' u C_K and takes
+// ArgTopK of its second row): the scoring pass has left pure low-bit logits; for the positions whose
+// 16-bit pairs are staged, logits and key are replaced by those of the 16-bit key.  One wave per
+// staged pair: lane = two channels, a wave reduction per query row.
+template <bool BF16>
+__global__ __launch_bounds__(256) void patch_staged_kernel(const uint16_t* __restrict__ q, int NR, int n_rows, float sm_scale,
+                                                           const uint16_t* __restrict__ slot, const int32_t* __restrict__ slot_idx,
+                                                           int k, int Nq, float* __restrict__ logits, size_t logit_stride,
+                                                           uint32_t* __restrict__ keys, size_t key_stride) {
+    const int row = blockIdx.y, j = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (j >= k) return;
+    const int pos = slot_idx[(size_t)row * k + j];
+    if (pos < 0 || pos >= Nq) return;                               // padding of a short selection
+    const uint32_t kk = reinterpret_cast<const uint32_t*>(slot + ((size_t)row * k + j) * 256)[lane];
+    const float k0 = widen16<BF16>(kk & 0xFFFFu), k1 = widen16<BF16>(kk >> 16);
+    float best = -INFINITY;
+    for (int r = 0; r < NR; ++r) {
+        const uint32_t qq = reinterpret_cast<const uint32_t*>(q + ((size_t)row * NR + r) * kD)[lane];
+        float acc = __builtin_fmaf(widen16<BF16>(qq & 0xFFFFu), k0, widen16<BF16>(qq >> 16) * k1);
+        acc = wave_sum(acc) * sm_scale;
+        if (lane == 0) logits[((size_t)row * NR + r) * logit_stride + pos] = acc;
+        if (r % n_rows == n_rows - 1) best = fmaxf(best, acc);
+    }
+    if (lane == 0) keys[(size_t)row * key_stride + pos] = float_to_key(best);
+}
+
 }  // namespace
+
+hipError_t launch_patch_staged(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, const uint16_t* slot,
+                               const int32_t* slot_idx, float* logits, size_t logit_stride, uint32_t* keys,
+                               size_t key_stride, hipStream_t stream) {
+    if (Nq <= 0 || L.topk <= 0) return hipSuccess;
+    const dim3 grid((L.topk + 3) / 4, L.rows), block(256);
+    if (L.bf16)
+        hipLaunchKernelGGL(patch_staged_kernel<true>, grid, block, 0, stream, (const uint16_t*)q, L.G * n_rows, n_rows, sm_scale,
+                           slot, slot_idx, L.topk, Nq, logits, logit_stride, keys, key_stride);
+    else
+        hipLaunchKernelGGL(patch_staged_kernel<false>, grid, block, 0, stream, (const uint16_t*)q, L.G * n_rows, n_rows, sm_scale,
+                           slot, slot_idx, L.topk, Nq, logits, logit_stride, keys, key_stride);
+    return hipGetLastError();
+}
 
 size_t select_logprob_scratch_floats(int rows, int G, int max_seq) {
     return (size_t)rows * G * ((max_seq + kSliceKeys - 1) / kSliceKeys) * 2;

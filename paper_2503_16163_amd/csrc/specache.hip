@@ -176,6 +176,8 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
     if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
         return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
+    if (c.select_cache != SPECACHE_SELECT_LOWBIT && c.select_cache != SPECACHE_SELECT_MIXED)
+        return fail(nullptr, SPECACHE_EINVAL, "select_cache must be SPECACHE_SELECT_LOWBIT or SPECACHE_SELECT_MIXED");
     if (c.select_form != SPECACHE_SELECT_MAX_LOGIT && c.select_form != SPECACHE_SELECT_MAX_LOGPROB)
         return fail(nullptr, SPECACHE_EINVAL, "select_form must be SPECACHE_SELECT_MAX_LOGIT or SPECACHE_SELECT_MAX_LOGPROB");
     if (c.group != 32 && c.group != 64) return fail(nullptr, SPECACHE_EINVAL, "group must be 32 or 64");
@@ -332,6 +334,15 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE);
         SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
                                   ctx->logit_stride, st));
+        // selection on the mixed cache: the positions staged by the layer's last gather are scored with
+        // their 16-bit keys (that slot is the one the coming attend reads; the next gather into it
+        // waits for this stream's next selection event, so it cannot overtake the patch)
+        if (ctx->cfg.select_cache == SPECACHE_SELECT_MIXED && L.last_gather_slot >= 0) {
+            const int sl = L.last_gather_slot;
+            if (L.gather_stream[sl] != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[sl], 0));
+            SPC_HIP(ctx, launch_patch_staged(L.view, q, n_rows, L.Nq, ctx->sm_scale, L.slot[sl], L.slot_idx[sl], ctx->logits,
+                                             ctx->logit_stride, ctx->keys, ctx->logit_stride, st));
+        }
         // several query heads per KV head and the log-probability form: the keys are rewritten from
         // the logits shifted by every head's log-sum-exp (one head: same order, nothing to do)
         if (ctx->cfg.select_form == SPECACHE_SELECT_MAX_LOGPROB && L.view.G > 1)

@@ -63,15 +63,16 @@ class Case:
     """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
-                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0):
+                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
         self.sample = sample if sample is not None else [(b, h) for b in range(B) for h in range(Hkv)]
         cap = max_seq or ((S + 64 + 63) // 64) * 64
-        self.one_bit_form, self.select_form = one_bit_form, select_form
+        self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
+        self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
-                                   select_form=select_form)
+                                   select_form=select_form, select_cache=select_cache)
         self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
         self.oc = {}
         self.step_k, self.step_v = [], []
@@ -164,7 +165,8 @@ class Case:
         for (b, h) in self.sample:
             c = self.oc[(b, h)]
             qh = q_bits[b, h * self.G:(h + 1) * self.G]                      # [G, rows, D]
-            ref_logits, sigma = c.scores(qh, self.sm_scale, self.select_form)
+            staged = self.staged_idx[b, h] if (self.select_cache and self.staged_idx is not None) else None
+            ref_logits, sigma = c.scores(qh, self.sm_scale, self.select_form, P=staged)
             if check_logits and nq:
                 got = logits_h[b, h * self.G:(h + 1) * self.G]
                 err = np.abs(got - ref_logits).max() / max(np.abs(ref_logits).max(), 1.0)
@@ -177,6 +179,8 @@ class Case:
             e = check_out(out_h[b, h * self.G:(h + 1) * self.G], ref_out, what=f"attend {(b, h)} step {t}")
             self.stats["max_out_err"] = max(self.stats["max_out_err"], e)
         self.prev_idx = idx_h
+        if do_gather:
+            self.staged_idx = idx_h
         self.last_q_bits = q_bits
         self.step_no += 1
         return idx_h, out_h

@@ -281,6 +281,24 @@ def test_log_probability_selection(Hq, Hkv, dtype, bits, g, n_rows):
         binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_form=3)
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g,form", [(2, 2, synth.FP16, 2, 32, 0), (8, 2, synth.BF16, 1, 32, 0), (4, 2, synth.FP16, 2, 64, 1)])
+def test_selection_on_the_mixed_cache(Hq, Hkv, dtype, bits, g, form):
+    """select_cache = SPECACHE_SELECT_MIXED: the staged positions are scored with their 16-bit keys (logits and
+    selection against the oracle's mixed-cache scores), alone and together with the log-probability form."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 1900, dtype, bits, g, 56, seed=2800 + Hq + g, select_form=form, select_cache=1)
+    try:
+        c.load()
+        for t in range(4):
+            c.decode_step()
+            c.append_token(t)
+        assert c.staged_idx is not None
+    finally:
+        c.close()
+    with pytest.raises(binding.SpeCacheError):
+        binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_cache=2)
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
