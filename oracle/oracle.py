@@ -125,8 +125,8 @@ class Cache:
             raise ValueError("oracle cache: invalid configuration")
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().orc_cache_destroy(self._h)
+        if getattr(self, "_h", None) and _lib is not None:   # at interpreter exit the module may be gone already
+            _lib.orc_cache_destroy(self._h)
             self._h = None
 
     def append(self, k_rows, v_rows):
