@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="M0", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
+    ap.add_argument("--topk", type=int, default=0,
+                    help="override k, the number of prefetched pairs per (batch, KV head) (the k sweep of Section 4.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
@@ -114,6 +116,8 @@ def main():
     B, Hq, Hkv, S, dtype, bits, g, k, layers = WORKLOADS[args.workload]
     if args.layers:
         layers = args.layers
+    if args.topk:
+        k = args.topk
     G, D, R = Hq // Hkv, 128, 64
     total_steps = args.warmup + 4 * args.steps + 2
     max_seq = ((S + total_steps + 63) // 64 + 1) * 64
