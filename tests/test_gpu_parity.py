@@ -391,6 +391,23 @@ def test_error_paths():
 
 # ---- the benchmark's full sizes, in the launch configuration bench.py times; the oracle mirrors a
 # ---- sample of (batch, KV head) rows, all of whose outputs are compared element by element.
+@pytest.mark.timeout(600)
+def test_very_long_row_with_the_largest_k():
+    """600000 keys in one row (close to the longest the library takes) and k = 4096, the largest: ArgTopK runs as 16
+    ranges of 37504 keys and a second launch over 65536 candidates, the attention as 1172 chunks of quantised tokens
+    plus 33 of 16-bit pairs (limit 1280)."""
+    from tests.harness import Case
+    c = Case(1, 1, 1, 600000, synth.BF16, 1, 64, 4096, seed=3100)
+    try:
+        c.load()
+        c.decode_step(check_logits=False)
+        c.append_token(0)
+        c.decode_step()
+        assert c.sc.counts(0)[1] >= 599872
+    finally:
+        c.close()
+
+
 FULL = {
     "config2": dict(B=1, Hq=32, Hkv=32, S=16384, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 0), (0, 13), (0, 31)]),
     "M0_7B_32k": dict(B=1, Hq=32, Hkv=32, S=32768, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 5), (0, 30)]),
