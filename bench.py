@@ -76,6 +76,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="M0", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
+    ap.add_argument("--filler-mb", type=int, default=0,
+                    help="EMULATION, not part of the method's path: after every layer's attend, stream this many MB of "
+                         "stand-in weights through a plain torch reduction on the main stream (a 7B layer reads about "
+                         "403 MB of fp16 weights per decode step), to see how much of the gather the rest of a model's "
+                         "layer would hide")
     ap.add_argument("--topk", type=int, default=0,
                     help="override k, the number of prefetched pairs per (batch, KV head) (the k sweep of Section 4.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -175,6 +180,8 @@ def main():
     idx = [[torch.full((B, Hkv, k), -1, dtype=torch.int32, device="cuda") for _ in range(2)] for _ in range(layers)]
     out = [torch.empty((B, Hq, 2, D), dtype=torch.float32, device="cuda") for _ in range(layers)]
     state = {"t": 0}
+    filler = torch.ones(args.filler_mb * (1 << 20) // 2, dtype=torch.float16, device="cuda") if args.filler_mb else None
+    filler_out = torch.empty((), dtype=torch.float16, device="cuda")
 
     def step_nonspec():
         t = state["t"]
@@ -198,6 +205,8 @@ def main():
                 sc.gather(L, idx[L][t % 2], (t + 1) % 2, side_s)
             slot = (t % 2) if (t > 0 and not args.no_gather) else -1
             sc.attend(L, q, 2, spec_k, spec_v, slot, out[L], main_s)
+            if filler is not None:
+                torch.sum(filler, dim=(0,), out=filler_out)
         state["t"] = t + 1
 
     for _ in range(args.warmup):
@@ -287,7 +296,7 @@ def main():
         "value": round(us_layer, 3), "unit": "us/layer-step", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
+        "data": "synthetic" if not args.filler_mb else f"synthetic; EMULATED rest of the layer: {args.filler_mb} MB streamed per layer",
         "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
                    "residual": R, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
