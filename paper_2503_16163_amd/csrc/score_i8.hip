@@ -32,14 +32,17 @@
 // steps, bytes are transposed with v_perm_b32 and handed to the lanes that own the B columns
 // through a wave-private LDS area; after the MFMAs the used blocks cross the same area once
 // more so that every lane finishes four consecutive tokens of one row (16-byte stores).
-// Measured on MI355X at 32 heads x 32768 keys, 2-bit codes: 14.0 us per launch (3.6 TB/s of
-// packed keys and metadata) against 19.0 us for the vector-ALU kernel, with 4.8 M instead of
-// 8.4 M vector instructions.  What bounds it now is the life of a wave, loads - fold -
-// exchange - MFMAs - exchange - stores with little to overlap inside one wave: taking out the
-// fold or the MFMAs does not change the time, six resident waves per SIMD instead of four
-// (the register cap below) give 0.9 us, an empty kernel of the same grid takes 4.5 us, and
-// waves that walk several tiles with the next tile's loads in flight were slower (fewer
-// waves, more registers).
+// Measured on MI355X at 32 heads x 32768 keys, 2-bit codes: 13.4 us per launch (3.8 TB/s of
+// packed keys and metadata; 4.7 TB/s counting the fp32 logits and keys it writes) against
+// 19.0 us for the vector-ALU kernel, with 4.4 M instead of 8.4 M vector instructions.  The
+// kernel is no longer bound by instruction issue: taking out the fold or the MFMAs does not
+// change its time, taking out the code loads or the stores does (-1.9 and -2.3 us), an empty
+// kernel of the same grid takes 4.5 us.  What helped on the way: accumulators of one token at
+// a time, so that a wave fits 64 registers and all eight waves a SIMD gets are resident at
+// once (14.8 us with four resident waves, 14.0 with six, 13.4 with eight).  What did not:
+// waves that walk several tiles with the next tile's loads in flight (15.4 - 18.3 us: fewer
+// waves, more registers), padding against LDS bank conflicts, and leaving out the key array
+// (ArgTopK ranking the logits costs it more than the store saves here).
 #include "kernels.h"
 #include "layout.h"
 
@@ -51,8 +54,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kWaves = 4;
 constexpr int kPieceStride = 36;                          // dwords: 32 channel quads of one byte plane + pad
 constexpr int kSubStride = 2 * 4 * kPieceStride + 8;      // dwords: [row][byte plane] of one sub-group + pad
-constexpr int kWaveDwords = 4 * kSubStride;               // >= 1024 dwords of result blocks
-static_assert(kWaveDwords >= 1024, "the result exchange reuses the multiplier area");
+constexpr int kWaveDwords = 4 * kSubStride;
+constexpr int kResBlock = 64 + 4;                         // dwords between the result blocks of (sub-group, row, half)
+static_assert(kWaveDwords >= 16 * kResBlock, "the result exchange reuses the multiplier area");
 
 // lane exchange patterns inside a row of 16 lanes
 constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
@@ -87,8 +91,8 @@ __device__ __forceinline__ void byte_planes(uint32_t y0, uint32_t y1, uint32_t y
 }
 
 template <int BITS, bool BF16>
-// at most 80 registers: six waves per SIMD
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(6, 8))) void score_i8_kernel(LayerView L, const uint16_t* __restrict__ q, int Nq,
+// at most 64 registers: all eight waves a SIMD gets are resident at once
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(8, 8))) void score_i8_kernel(LayerView L, const uint16_t* __restrict__ q, int Nq,
                                                                float sm_scale, float* __restrict__ logits,
                                                                size_t logit_stride, uint32_t* __restrict__ keys,
                                                                size_t key_stride) {
@@ -199,17 +203,19 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(6, 
     __builtin_amdgcn_wave_barrier();                 // every lane has read its B operands: the area is free
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    // ---- the contraction: per (token half hf, token j of the lane's four) two k-steps, two rows.
+    // ---- the contraction: per token (half hf, j of the lane's four) two k-steps, two rows.
     // Result register v of lane (column n, quarter qq) is MFMA row 4 qq + v: sub-group qq of the
     // wave, quad lane v, i.e. token 32 (sub0 + qq) + 8 v + 4 hf + j.  It is wanted where the
-    // column's sub-group is qq too; those blocks go to [sub-group][row][hf][byte p][v][j].
+    // column's sub-group is qq too; those quads go to block (sub-group, row, hf) of the area as
+    // [byte p][token j][quad lane v], the blocks 4 dwords further apart than their size so that
+    // the lanes that read one position of 16 different blocks hit 16 different banks.
 #pragma unroll
-    for (int hf = 0; hf < 2; ++hf) {
-        v4i acc[4][2];
+    for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+        for (int j = 0; j < 4; ++j) {
+            v4i acc[2];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int ks = 0; ks < 2; ++ks) {
                 v4i a;
                 if constexpr (BITS == 2) {
                     const uint32_t w = comp(cw[ks][hf], j), t = w >> 4;
@@ -220,17 +226,14 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(6, 
                 }
 #pragma unroll
                 for (int r = 0; r < 2; ++r)
-                    acc[j][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bop[ks][r], ks == 0 ? (v4i){0, 0, 0, 0} : acc[j][r], 0, 0, 0);
+                    acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bop[ks][r], ks == 0 ? (v4i){0, 0, 0, 0} : acc[r], 0, 0, 0);
             }
-        if (sgB == qd) {
+            if (sgB == qd) {
 #pragma unroll
-            for (int r = 0; r < 2; ++r)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    *reinterpret_cast<v4i*>(area + ((((qd * 2 + r) * 2 + hf) * 4 + p) * 4 + v) * 4) =
-                        (v4i){acc[0][r][v], acc[1][r][v], acc[2][r][v], acc[3][r][v]};
+                for (int r = 0; r < 2; ++r)
+                    *reinterpret_cast<v4i*>(area + ((qd * 2 + r) * 2 + hf) * kResBlock + (p * 4 + j) * 4) = acc[r];
+            }
         }
-    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -238,10 +241,12 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(6, 
     // ---- every lane finishes four consecutive tokens of one row: lane = (sub-group sgO, row rO,
     // ---- quad lane vO, half hfO), 8 lanes cover the 32 tokens of a sub-group in order
     const int sgO = lane >> 4, rO = (lane >> 3) & 1, vO = (lane >> 1) & 3, hfO = lane & 1;
-    v4i s[4];
+    int s[4][4];   // [byte p][token j]
+    const uint32_t* blk = area + ((sgO * 2 + rO) * 2 + hfO) * kResBlock + vO;
 #pragma unroll
     for (int pp = 0; pp < 4; ++pp)
-        s[pp] = *reinterpret_cast<const v4i*>(area + ((((sgO * 2 + rO) * 2 + hfO) * 4 + pp) * 4 + vO) * 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s[pp][j] = (int)blk[(pp * 4 + j) * 4];
     const float2 f = fin[wave][sgO][rO];
     float o[4];
 #pragma unroll
