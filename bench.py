@@ -86,6 +86,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
+    ap.add_argument("--side-streams", type=int, default=0,
+                    help="side streams the gathers alternate over by layer; 0 = 2 (two gathers share the link and cover "
+                         "each other's launch gaps) unless a fetched pair stands for 384 or more scored keys, where the "
+                         "gather has time to spare and one stream disturbs the other kernels less")
     ap.add_argument("--variant", default="speculative", choices=["speculative", "nonspec"],
                     help="nonspec: the non-speculative fetching of Section 4.4 (select on the current token, one query "
                          "row, gather on the main stream before attend): the whole link time is exposed")
@@ -139,7 +143,8 @@ def main():
                 raise
             layers = max(1, layers // 2)   # the pinned host store did not fit: fewer layers
     main_s = torch.cuda.current_stream()
-    side_s = main_s if args.serial_gather else torch.cuda.Stream()
+    n_side = args.side_streams if args.side_streams > 0 else (1 if G * S >= 384 * k else 2)
+    side_list = [main_s] if args.serial_gather else [torch.cuda.Stream() for _ in range(n_side)]
 
     # ---- load the prompt: the same synthetic K/V tensor serves every layer ----------
     # This is the Quant + Offload of the prefilling procedure (Appendix A), timed per layer: the bulk
@@ -202,7 +207,7 @@ def main():
             sc.quantize_append(L, step_k[t], step_v[t], 1, main_s)
             sc.score_topk(L, q, 2, idx[L][t % 2], main_s)
             if gather and not args.no_gather:
-                sc.gather(L, idx[L][t % 2], (t + 1) % 2, side_s)
+                sc.gather(L, idx[L][t % 2], (t + 1) % 2, side_list[L % len(side_list)])
             slot = (t % 2) if (t > 0 and not args.no_gather) else -1
             sc.attend(L, q, 2, spec_k, spec_v, slot, out[L], main_s)
             if filler is not None:
@@ -300,7 +305,8 @@ def main():
         "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
                    "residual": R, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
-                                   "main stream, gather of the next step's pairs on a side stream"},
+                                   "main stream, gather of the next step's pairs on side streams",
+                   "side_streams": len(side_list) if not args.serial_gather else 0},
         "score_topk_attend_us": breakdown["score_topk_attend"],
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "kernel_us_no_gather": per_kernel_ng,
@@ -311,6 +317,9 @@ def main():
         "attend_hbm_gbs": round(attend_bytes / (attend_us * 1e-6) / 1e9, 1),
         "gather_gbs": (round(B * Hkv * k * 512 / (per_kernel_us["gather"] * 1e-6) / 1e9, 2)
                        if per_kernel_us["gather"] else None),
+        # with two side streams two gather kernels run at a time: the link carries one layer's pairs per layer-step
+        "link_gbs_over_step": (round(B * Hkv * k * 512 / (us_layer * 1e-6) / 1e9, 2)
+                               if per_kernel_us["gather"] and args.variant == "speculative" else None),
         "roofline": roofline,
     }
 

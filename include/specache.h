@@ -157,6 +157,9 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
  * hot calls must stay alive until the context is destroyed: a later call may
  * still record an event on it.
  * Reusing a slot discards what it held (the paper's eviction).
+ * Callers that step several layers do well to alternate two side streams by layer:
+ * two gathers then share the link and cover each other's launch gaps (the library
+ * notices the alternation and paces each gather accordingly).
  * Errors: EINVAL (slot not 0/1, null idx, bad layer).
  */
 int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_t slot, void* side_stream);

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ h
 }  // namespace
 
 hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
-                         hipStream_t stream) {
+                         bool link_shared, hipStream_t stream) {
     const int total = L.rows * L.topk;
     // 16 workgroups x 4 reads per lane = 256 KB of host reads in flight, issued at raised wave
     // priority.  Measured on MI355X at 32 heads x 256 pairs per layer: beside the other kernels
@@ -68,7 +68,12 @@ hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_
     // with two, 154 with three.
     constexpr int kMaxGrid = 16;
     const double keys_per_pair = (double)L.G * Nq / (L.topk > 0 ? L.topk : 1);
-    const int in_flight = keys_per_pair >= 384.0 ? 2 : keys_per_pair >= 192.0 ? 3 : 4;
+    int in_flight = keys_per_pair >= 384.0 ? 2 : keys_per_pair >= 192.0 ? 3 : 4;
+    // The caller spreads its gathers over several streams, so two of them are in flight at a time and
+    // each other's launch gaps are covered: with two reads per lane each the link is as busy as one
+    // gather keeps it alone, 50 GB/s, and the other kernels are disturbed less (7B shape at 32 k: whole
+    // step 83.5 us per layer with two streams x two reads, 85.6 with x three, 93 with one stream x four).
+    if (link_shared && in_flight > 2) in_flight = 2;
     int grid = (total + 8 * in_flight - 1) / (8 * in_flight);
     if (grid > kMaxGrid) grid = kMaxGrid;
     if (grid < 1) return hipSuccess;

@@ -3,6 +3,7 @@
 // returns the hipGetLastError() of its launches.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace specache {
@@ -30,6 +31,25 @@ hipError_t launch_flush(const LayerView& L, const void* k_new, const void* v_new
 // copy the n_new tokens to the host store (all) and to the ring (tokens >= ring_from)
 hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0,
                               int ring_from, hipStream_t stream);
+
+// Per-kernel timing of the scoring pass: a pair of events that the next kernel launched through
+// SPC_LAUNCH on this thread carries on its own dispatch packet (start and stop of that kernel, as a
+// profiler sees them) instead of event records around the launch, which would add the stream's
+// marker packets and the launch gap to the figure.
+struct LaunchEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+LaunchEvents& pending_launch_events();
+#define SPC_LAUNCH(kernel, grid, block, stream, ...)                                                          \
+    do {                                                                                                      \
+        specache::LaunchEvents& le_ = specache::pending_launch_events();                                      \
+        if (le_.stop) {                                                                                       \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, le_.start, le_.stop, 0, __VA_ARGS__);       \
+            le_ = specache::LaunchEvents{};                                                                   \
+        } else {                                                                                              \
+            hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                  \
+        }                                                                                                     \
+    } while (0)
 
 // score: logits [rows*G*n_rows][logit_stride] fp32 and keys [rows][key_stride] u32 for i < Nq
 hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
@@ -65,9 +85,9 @@ hipError_t launch_topk(int rows, int Nq, int k, const uint32_t* keys, size_t key
                        const TopkScratch& scratch, hipStream_t stream);
 
 // gather rows idx[row][j] of the host store into slot [rows][k][256] and slot_idx [rows][k];
-// Nq (quantised positions of the layer) only paces the transfer
+// Nq (quantised positions of the layer) and link_shared (another gather runs beside this one) only pace the transfer
 hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_t* slot, int32_t* slot_idx,
-                         hipStream_t stream);
+                         bool link_shared, hipStream_t stream);
 
 // attend: partial pass + combine.  slot/slot_idx may be null (nothing prefetched).
 struct AttendScratch {

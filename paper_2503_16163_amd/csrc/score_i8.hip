@@ -275,8 +275,8 @@ hipError_t launch_score_i8(const LayerView& L, const void* q, int Nq, float sm_s
         return hipErrorInvalidValue;
     const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kWaves);
 #define SPC_I8(B_, F_)                                                                                         \
-    hipLaunchKernelGGL((score_i8_kernel<B_, F_>), grid, block, 0, stream, L, (const uint16_t*)q, Nq, sm_scale, \
-                       logits, logit_stride, keys, key_stride)
+    SPC_LAUNCH((score_i8_kernel<B_, F_>), grid, block, stream, L, (const uint16_t*)q, Nq, sm_scale, logits, \
+               logit_stride, keys, key_stride)
     if (L.bits == 2) { if (L.bf16) SPC_I8(2, true); else SPC_I8(2, false); }
     else             { if (L.bf16) SPC_I8(1, true); else SPC_I8(1, false); }
 #undef SPC_I8

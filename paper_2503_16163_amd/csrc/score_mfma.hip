@@ -277,10 +277,10 @@ hipError_t launch_case(const LayerView& L, const void* q, int Nq, float sm_scale
                        uint32_t* keys, size_t key_stride, hipStream_t stream) {
     const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kWaves);
     if (L.bf16)
-        hipLaunchKernelGGL((score_mfma_kernel<BITS, G, NROWS, true>), grid, block, 0, stream, L, (const uint16_t*)q, Nq,
+        SPC_LAUNCH((score_mfma_kernel<BITS, G, NROWS, true>), grid, block, stream, L, (const uint16_t*)q, Nq,
                            sm_scale, logits, logit_stride, keys, key_stride);
     else
-        hipLaunchKernelGGL((score_mfma_kernel<BITS, G, NROWS, false>), grid, block, 0, stream, L, (const uint16_t*)q, Nq,
+        SPC_LAUNCH((score_mfma_kernel<BITS, G, NROWS, false>), grid, block, stream, L, (const uint16_t*)q, Nq,
                            sm_scale, logits, logit_stride, keys, key_stride);
     return hipGetLastError();
 }

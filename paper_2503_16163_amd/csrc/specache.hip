@@ -17,6 +17,13 @@
 
 using namespace specache;
 
+namespace specache {
+LaunchEvents& pending_launch_events() {
+    static thread_local LaunchEvents le;
+    return le;
+}
+}  // namespace specache
+
 namespace {
 
 struct Layer {
@@ -62,6 +69,8 @@ struct specache_ctx {
     TopkScratch topk_scratch{};
     int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
     uint64_t seq = 0;            // counts the calls that order streams (see Layer)
+    hipStream_t last_gather_stream = nullptr;   // stream of the previous specache_gather, of any layer
+    bool last_gather_stream_set = false;
     std::string err;
     // optional per-kernel timing: (start, stop) event pairs recorded around each launch
     bool timing = false;
@@ -89,26 +98,41 @@ int fail_hip(specache_ctx* ctx, hipError_t e, const char* what) {
         if (e_ != hipSuccess) return fail_hip(ctx, e_, #call); \
     } while (0)
 
-// Brackets one launcher call with a pair of timing events when timing is on.
+// Brackets one launcher call with a pair of timing events when timing is on.  on_kernel: the
+// events are handed to the launcher's first SPC_LAUNCH instead, which times that kernel alone.
 struct TimedLaunch {
     specache_ctx* ctx;
     hipStream_t st;
     int kind;
+    bool on_kernel;
     hipEvent_t a = nullptr, b = nullptr;
     static hipEvent_t take(specache_ctx* c) {
         if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
         hipEvent_t e = nullptr;
         return hipEventCreate(&e) == hipSuccess ? e : nullptr;
     }
-    TimedLaunch(specache_ctx* c, hipStream_t s, int k) : ctx(c), st(s), kind(k) {
+    TimedLaunch(specache_ctx* c, hipStream_t s, int k, bool kernel_events = false)
+        : ctx(c), st(s), kind(k), on_kernel(kernel_events) {
         if (!c->timing) return;
         a = take(c);
         b = take(c);
-        if (a) (void)hipEventRecord(a, st);
+        if (!a || !b) return;
+        if (on_kernel) pending_launch_events() = LaunchEvents{a, b};
+        else (void)hipEventRecord(a, st);
     }
     ~TimedLaunch() {
         if (!a || !b) return;
-        (void)hipEventRecord(b, st);
+        if (on_kernel) {
+            LaunchEvents& le = pending_launch_events();
+            if (le.stop) {   // no kernel took them (nothing was launched): no span
+                le = LaunchEvents{};
+                ctx->ev_pool.push_back(a);
+                ctx->ev_pool.push_back(b);
+                return;
+            }
+        } else {
+            (void)hipEventRecord(b, st);
+        }
         ctx->spans.push_back({kind, a, b});
     }
 };
@@ -331,7 +355,7 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     if (L.last_gather_idx == topk_idx_out && L.last_gather_slot >= 0)
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
     if (L.Nq > 0) {
-        TimedLaunch t(ctx, st, SPECACHE_K_SCORE);
+        TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
         SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
                                   ctx->logit_stride, st));
         // selection on the mixed cache: the positions staged by the layer's last gather are scored with
@@ -385,7 +409,11 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     }
     {
         TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
-        SPC_HIP(ctx, launch_gather(L.view, L.Nq, idx, L.slot[slot], L.slot_idx[slot], st));
+        // a caller that alternates side streams has two gathers on the link at a time
+        const bool link_shared = ctx->last_gather_stream_set && ctx->last_gather_stream != st;
+        SPC_HIP(ctx, launch_gather(L.view, L.Nq, idx, L.slot[slot], L.slot_idx[slot], link_shared, st));
+        ctx->last_gather_stream = st;
+        ctx->last_gather_stream_set = true;
     }
     SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
     L.gather_stream[slot] = st;

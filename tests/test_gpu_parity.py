@@ -299,6 +299,57 @@ def test_selection_on_the_mixed_cache(Hq, Hkv, dtype, bits, g, form):
         binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_cache=2)
 
 
+def test_layers_alternating_two_side_streams():
+    """Four layers stepped in turn, their gathers alternating between two side streams (two gathers are then in
+    flight at a time and the library paces them for a shared link).  Every layer holds the same cache and gets
+    the same queries, so every layer's selection and output must match the one oracle cache."""
+    from oracle import oracle as orc
+    from tests.harness import check_out, check_topk, to_dev
+    layers, Hq, S, k, dtype, seed = 4, 3, 2300, 72, synth.FP16, 2900
+    sc = binding.SpeCache(layers, 1, Hq, Hq, 2, 32, 2432, k, dtype)
+    try:
+        kb, vb = synth.make_kv(seed, 1, Hq, S, 128, dtype)
+        oc = [orc.Cache(128, 2, 32, 64, dtype) for _ in range(Hq)]
+        for h in range(Hq):
+            oc[h].append(kb[0, h], vb[0, h])
+        main, sides = torch.cuda.current_stream(), [torch.cuda.Stream(), torch.cuda.Stream()]
+        for L in range(layers):
+            sc.quantize_append(L, to_dev(kb, dtype), to_dev(vb, dtype), S)
+        idx = [[torch.full((1, Hq, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)] for _ in range(layers)]
+        out = [torch.empty((1, Hq, 2, 128), dtype=torch.float32, device="cuda") for _ in range(layers)]
+        prev = None
+        sm = 1.0 / np.sqrt(128.0)
+        for t in range(4):
+            q_bits = synth.make_queries(seed, 1, Hq, 128, dtype, n_rows=2, sub=t)
+            ks_bits, vs_bits = synth.make_spec_kv(seed, 1, Hq, 128, dtype, sub=t)
+            nk, nv = synth.make_step_kv(seed, t, 1, Hq, 128, dtype)
+            q, ks, vs = to_dev(q_bits, dtype), to_dev(ks_bits, dtype), to_dev(vs_bits, dtype)
+            nkd, nvd = to_dev(nk, dtype), to_dev(nv, dtype)
+            for L in range(layers):
+                sc.quantize_append(L, nkd, nvd, 1, main)
+                sc.score_topk(L, q, 2, idx[L][t % 2], main)
+                sc.gather(L, idx[L][t % 2], (t + 1) % 2, sides[L % 2])
+                sc.attend(L, q, 2, ks, vs, (t % 2) if t > 0 else -1, out[L], main)
+            torch.cuda.synchronize()
+            for h in range(Hq):
+                oc[h].append(nk[0, h], nv[0, h])
+            cur = [idx[L][t % 2].cpu().numpy() for L in range(layers)]
+            for h in range(Hq):
+                qh = q_bits[0, h:h + 1]
+                _, sigma = oc[h].scores(qh, sm)
+                ref = oc[h].attend(qh, sm, P=prev[0][0, h] if prev is not None else None, k_spec=ks_bits[0, h, 0],
+                                   v_spec=vs_bits[0, h, 0])
+                for L in range(layers):
+                    check_topk(sigma, cur[L][0, h], k, what=f"layer {L} head {h} step {t}")
+                    check_out(out[L].cpu().numpy()[0, h:h + 1], ref, what=f"layer {L} head {h} step {t}")
+            for L in range(1, layers):
+                assert np.array_equal(cur[L], cur[0])
+            prev = cur
+    finally:
+        torch.cuda.synchronize()
+        sc.close()
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
