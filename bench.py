@@ -105,6 +105,11 @@ def main():
     ap.add_argument("--select-cache", default="lowbit", choices=["lowbit", "mixed"],
                     help="which logits ArgTopK ranks: pure low-bit (default) or the mixed cache's (the staged positions "
                          "are scored with their 16-bit keys: one more small kernel per layer-step)")
+    ap.add_argument("--select-stream", default="auto", choices=["auto", "own", "main"],
+                    help="where ArgTopK runs: on a stream of the library's own beside the attention kernels "
+                         "(specache_config.async_select) or on the main stream; auto = own when several layers are "
+                         "stepped speculatively, main for the one-layer workloads and the non-speculative variant, where "
+                         "the extra stream calls cost more than they hide")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -132,12 +137,15 @@ def main():
     max_seq = ((S + total_steps + 63) // 64 + 1) * 64
     seed = 1000
 
+    async_select = 1 if (args.select_stream == "own" or (args.select_stream == "auto" and layers > 1 and
+                                                          args.variant == "speculative")) else 0
     sc = None
     while sc is None:
         try:
             sc = binding.SpeCache(layers, B, Hq, Hkv, bits, g, max_seq, k, dtype, residual=R,
                                   select_form=1 if args.select == "logprob" else 0,
-                                  select_cache=1 if args.select_cache == "mixed" else 0)
+                                  select_cache=1 if args.select_cache == "mixed" else 0,
+                                  async_select=async_select)
         except binding.SpeCacheError as e:
             if e.code != binding.ENOMEM or layers == 1:
                 raise
@@ -306,7 +314,8 @@ def main():
                    "residual": R, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
                                    "main stream, gather of the next step's pairs on side streams",
-                   "side_streams": len(side_list) if not args.serial_gather else 0},
+                   "side_streams": len(side_list) if not args.serial_gather else 0,
+                   "async_select": bool(async_select)},
         "score_topk_attend_us": breakdown["score_topk_attend"],
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "kernel_us_no_gather": per_kernel_ng,

@@ -86,6 +86,15 @@ typedef struct specache_config {
                            SPECACHE_SELECT_MIXED, those of the mixed cache of Eq. 1: the
                            positions staged by the layer's last specache_gather are scored
                            with their 16-bit keys (Appendix A "Decoding" computes one A)  */
+    int32_t async_select; /* 0: specache_score_topk runs entirely on the caller's stream.
+                           1: ArgTopK runs on a stream of the library's own, after the
+                           scoring pass, so that the caller's stream goes straight on to
+                           specache_attend (which does not need the selection) while the
+                           positions are ranked beside it.  specache_gather orders itself
+                           after the selection either way; on the caller's stream
+                           topk_idx_out is complete only after the next
+                           specache_score_topk call (of any layer), which waits for it,
+                           or after a device synchronise                               */
 } specache_config;
 
 typedef struct specache_ctx specache_ctx;
@@ -135,7 +144,8 @@ int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new
  * packed keys (read once for all rows and heads of a KV head) and kept in the
  * context for the following specache_attend.  The selection score of position i
  * for a KV head is the maximum over its Hq/Hkv query heads of the LAST row's
- * logit.  topk_idx_out: device int32 [B, Hkv, k]; receives the min(k, Nq)
+ * logit.  topk_idx_out: device int32 [B, Hkv, k] (see async_select for when it is
+ * complete); receives the min(k, Nq)
  * positions with the largest selection score (ties to the lower index) in
  * ascending index order, the rest -1.
  * Errors: EINVAL, ESTATE (no call order requirement fails here; Nq = 0 is

@@ -25,7 +25,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "batch", "n_q_heads", "n_kv_heads", "head_dim", "bits",
                                          "group", "residual", "max_seq", "topk", "dtype")] + [("sm_scale", C.c_float),
                                                                                  ("one_bit_form", C.c_int32), ("select_form", C.c_int32),
-                                                                                 ("select_cache", C.c_int32)]
+                                                                                 ("select_cache", C.c_int32), ("async_select", C.c_int32)]
 
 
 class SpeCacheError(RuntimeError):
@@ -97,9 +97,9 @@ class SpeCache:
     """Owner of a specache_ctx; methods mirror the C calls one to one."""
 
     def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, bits, group, max_seq, topk, dtype,
-                 residual=64, head_dim=128, sm_scale=0.0, one_bit_form=0, select_form=0, select_cache=0):
+                 residual=64, head_dim=128, sm_scale=0.0, one_bit_form=0, select_form=0, select_cache=0, async_select=0):
         self.cfg = Config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, bits, group, residual, max_seq,
-                          topk, dtype, sm_scale, one_bit_form, select_form, select_cache)
+                          topk, dtype, sm_scale, one_bit_form, select_form, select_cache, async_select)
         self._ctx = C.c_void_p()
         rc = lib().specache_create(C.byref(self.cfg), C.byref(self._ctx))
         if rc != OK:

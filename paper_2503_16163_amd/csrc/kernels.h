@@ -32,20 +32,24 @@ hipError_t launch_flush(const LayerView& L, const void* k_new, const void* v_new
 hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0,
                               int ring_from, hipStream_t stream);
 
-// Per-kernel timing of the scoring pass: a pair of events that the next kernel launched through
+// Per-kernel timing of the scoring pass and of ArgTopK: a pair of events that the next kernel launched through
 // SPC_LAUNCH on this thread carries on its own dispatch packet (start and stop of that kernel, as a
 // profiler sees them) instead of event records around the launch, which would add the stream's
 // marker packets and the launch gap to the figure.
 struct LaunchEvents {
     hipEvent_t start = nullptr, stop = nullptr;
+    int launches = 1;   // kernels the pair spans: the first carries start, the last stop
 };
 LaunchEvents& pending_launch_events();
 #define SPC_LAUNCH(kernel, grid, block, stream, ...)                                                          \
     do {                                                                                                      \
         specache::LaunchEvents& le_ = specache::pending_launch_events();                                      \
         if (le_.stop) {                                                                                       \
-            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, le_.start, le_.stop, 0, __VA_ARGS__);       \
-            le_ = specache::LaunchEvents{};                                                                   \
+            const bool last_ = le_.launches <= 1;                                                             \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, stream, le_.start, last_ ? le_.stop : nullptr, 0,   \
+                                  __VA_ARGS__);                                                               \
+            if (last_) le_ = specache::LaunchEvents{};                                                        \
+            else { le_.start = nullptr; --le_.launches; }                                                     \
         } else {                                                                                              \
             hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);                                  \
         }                                                                                                     \

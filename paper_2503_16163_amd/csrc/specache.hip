@@ -46,7 +46,8 @@ struct Layer {
     uint64_t attend_seq[2] = {0, 0};     // 0: no attend has read the slot
     hipEvent_t idx_ready = nullptr;
     bool idx_ready_recorded = false;
-    hipStream_t idx_ready_stream = nullptr;
+    hipStream_t idx_ready_stream = nullptr;       // where idx_ready was recorded
+    hipStream_t select_origin_stream = nullptr;   // the stream score_topk was called on (the same, unless ArgTopK runs aside)
     uint64_t idx_ready_seq = 0;
     const int32_t* last_gather_idx = nullptr;
     int last_gather_slot = -1;
@@ -71,6 +72,12 @@ struct specache_ctx {
     uint64_t seq = 0;            // counts the calls that order streams (see Layer)
     hipStream_t last_gather_stream = nullptr;   // stream of the previous specache_gather, of any layer
     bool last_gather_stream_set = false;
+    // ArgTopK on a stream of the library's own (async_select): the scoring pass stays on the caller's
+    // stream, which goes on to the attention kernels while the selection runs beside them
+    bool async_select = false;
+    hipStream_t select_stream = nullptr;
+    hipEvent_t scored = nullptr;            // scoring pass done (recorded on the caller's stream)
+    hipEvent_t last_select = nullptr;       // idx_ready of the most recent selection: it has read ctx->keys
     std::string err;
     // optional per-kernel timing: (start, stop) event pairs recorded around each launch
     bool timing = false;
@@ -165,6 +172,8 @@ void free_all(specache_ctx* ctx) {
     for (auto& sp : ctx->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     (void)hipFree(ctx->logits);
+    if (ctx->select_stream) (void)hipStreamDestroy(ctx->select_stream);
+    if (ctx->scored) (void)hipEventDestroy(ctx->scored);
     (void)hipFree(ctx->keys);
     (void)hipFree(ctx->lse);
     (void)hipFree(ctx->scratch.part_o);
@@ -200,6 +209,7 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
     if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
         return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
+    if (c.async_select != 0 && c.async_select != 1) return fail(nullptr, SPECACHE_EINVAL, "async_select must be 0 or 1");
     if (c.select_cache != SPECACHE_SELECT_LOWBIT && c.select_cache != SPECACHE_SELECT_MIXED)
         return fail(nullptr, SPECACHE_EINVAL, "select_cache must be SPECACHE_SELECT_LOWBIT or SPECACHE_SELECT_MIXED");
     if (c.select_form != SPECACHE_SELECT_MAX_LOGIT && c.select_form != SPECACHE_SELECT_MAX_LOGPROB)
@@ -274,6 +284,11 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
             SPC_ALLOC(hipEventCreateWithFlags(&L.attended[s], kOrderEventFlags));
         }
         SPC_ALLOC(hipEventCreateWithFlags(&L.idx_ready, kOrderEventFlags));
+    }
+    ctx->async_select = c.async_select != 0;
+    if (ctx->async_select) {
+        SPC_ALLOC(hipStreamCreateWithFlags(&ctx->select_stream, hipStreamNonBlocking));
+        SPC_ALLOC(hipEventCreateWithFlags(&ctx->scored, kOrderEventFlags));
     }
     ctx->logit_stride = cap;
     SPC_ALLOC(hipMalloc((void**)&ctx->logits, (size_t)rows * G * 2 * cap * 4));
@@ -351,9 +366,12 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)stream;
+    hipStream_t tk = ctx->async_select ? ctx->select_stream : st;   // where ArgTopK runs
     // a gather still reading this index buffer must finish before it is overwritten
     if (L.last_gather_idx == topk_idx_out && L.last_gather_slot >= 0)
-        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
+        SPC_HIP(ctx, hipStreamWaitEvent(tk, L.gathered[L.last_gather_slot], 0));
+    // the key array is shared by all layers: the previous selection, running aside, must have read it
+    if (ctx->async_select && ctx->last_select) SPC_HIP(ctx, hipStreamWaitEvent(st, ctx->last_select, 0));
     if (L.Nq > 0) {
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
         SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
@@ -373,14 +391,20 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
             SPC_HIP(ctx, launch_select_logprob(L.view, n_rows, L.Nq, ctx->logits, ctx->logit_stride, ctx->lse, ctx->keys,
                                                ctx->logit_stride, st));
     }
-    {
-        TimedLaunch t(ctx, st, SPECACHE_K_TOPK);
-        SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out,
-                                 ctx->topk_scratch, st));
+    if (ctx->async_select) {
+        SPC_HIP(ctx, hipEventRecord(ctx->scored, st));
+        SPC_HIP(ctx, hipStreamWaitEvent(tk, ctx->scored, 0));
     }
-    SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
+    {
+        TimedLaunch t(ctx, tk, SPECACHE_K_TOPK, /*kernel_events=*/true);
+        SPC_HIP(ctx, launch_topk(L.view.rows, L.Nq, ctx->cfg.topk, ctx->keys, ctx->logit_stride, topk_idx_out,
+                                 ctx->topk_scratch, tk));
+    }
+    SPC_HIP(ctx, hipEventRecord(L.idx_ready, tk));
+    ctx->last_select = L.idx_ready;
     L.idx_ready_recorded = true;
-    L.idx_ready_stream = st;
+    L.idx_ready_stream = tk;
+    L.select_origin_stream = st;
     L.idx_ready_seq = ++ctx->seq;
     ctx->scored_layer = layer;
     ctx->scored_rows = n_rows;
@@ -397,7 +421,7 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     hipStream_t st = (hipStream_t)side_stream;
     if (L.idx_ready_recorded && st != L.idx_ready_stream) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
     if (L.attend_seq[slot] != 0 && L.attend_stream[slot] != st) {
-        const bool behind_idx_ready = L.idx_ready_recorded && L.attend_stream[slot] == L.idx_ready_stream &&
+        const bool behind_idx_ready = L.idx_ready_recorded && L.attend_stream[slot] == L.select_origin_stream &&
                                       L.attend_seq[slot] < L.idx_ready_seq;
         if (!L.attended_recorded[slot] && !behind_idx_ready) {
             // a second gather into the slot without a new score_topk in between: record now, on the
@@ -447,7 +471,7 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
         L.attend_stream[slot] = st;
         L.attend_seq[slot] = ++ctx->seq;
         L.attended_recorded[slot] = false;
-        if (!(L.idx_ready_recorded && st == L.idx_ready_stream)) {
+        if (!(L.idx_ready_recorded && st == L.select_origin_stream)) {
             SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
             L.attended_recorded[slot] = true;
         }

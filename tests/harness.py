@@ -63,7 +63,7 @@ class Case:
     """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
-                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0):
+                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0, async_select=0):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
@@ -72,7 +72,7 @@ class Case:
         self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
         self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
-                                   select_form=select_form, select_cache=select_cache)
+                                   select_form=select_form, select_cache=select_cache, async_select=async_select)
         self.k_bits, self.v_bits = synth.make_kv(seed, B, Hkv, S, self.D, dtype, n_outlier=n_outlier)
         self.oc = {}
         self.step_k, self.step_v = [], []

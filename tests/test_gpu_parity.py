@@ -350,6 +350,35 @@ def test_layers_alternating_two_side_streams():
         sc.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g,form,mixed", [(2, 2, synth.FP16, 2, 32, 0, 0), (8, 2, synth.BF16, 1, 32, 1, 1),
+                                                             (4, 2, synth.FP16, 2, 64, 0, 1)])
+def test_selection_on_a_stream_of_its_own(Hq, Hkv, dtype, bits, g, form, mixed):
+    """async_select = 1: ArgTopK runs beside the attention kernels on a stream of the library.  Same results as on
+    the caller's stream, through the speculative flow, the non-speculative one (gather on the main stream) and across
+    flushes (the shared key array is written by the next scoring pass only after the selection has read it)."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 1700, dtype, bits, g, 48, seed=3000 + Hq + g, select_form=form, select_cache=mixed, async_select=1)
+    try:
+        c.load()
+        for t in range(40):
+            c.append_token(t)
+            if t % 8 == 0 or t > 36:
+                c.decode_step()
+            else:
+                c.decode_step(check_logits=False)
+        c.check_quantized()
+    finally:
+        c.close()
+    c = Case(1, 2, 2, 900, synth.FP16, 2, 32, 24, seed=3050, n_rows=1, async_select=1)
+    try:
+        c.load()
+        for t in range(3):
+            c.append_token(t)
+            c.nonspec_step()
+    finally:
+        c.close()
+
+
 def test_short_cache_edges():
     """Nq = 0 (everything still in the residual), k > Nq, and a cache of one token."""
     from tests.harness import Case
