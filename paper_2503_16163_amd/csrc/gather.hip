@@ -70,14 +70,21 @@ hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_
     const double keys_per_pair = (double)L.G * Nq / (L.topk > 0 ? L.topk : 1);
     int in_flight = keys_per_pair >= 384.0 ? 2 : keys_per_pair >= 192.0 ? 3 : 4;
     // The caller spreads its gathers over several streams, so two of them are in flight at a time and
-    // each other's launch gaps are covered: with two reads per lane each the link is as busy as one
-    // gather keeps it alone, 50 GB/s, and the other kernels are disturbed less (7B shape at 32 k: whole
-    // step 83.5 us per layer with two streams x two reads, 85.6 with x three, 93 with one stream x four).
-    if (link_shared && in_flight > 2) in_flight = 2;
+    // each other's launch gaps are covered.  Each then gets one read per lane and up to 32 workgroups
+    // (the same 128 KB in flight as 16 workgroups x 2 reads, spread over more compute units): the link
+    // carries 53-55 GB/s over the step, more than one gather reaches alone, and the other kernels are
+    // disturbed less.  Whole step at the 7B shape at 32 k, us per layer: one stream x 16 workgroups x 4
+    // reads 93; two streams x 16 x 2: 82.4; x 20 x 2: 80.5; x 32 x 1: 78.3; x 40 x 1: 77.6 - 81.9;
+    // x 48 x 1: 85.6.
+    int max_grid = kMaxGrid;
+    if (link_shared) {
+        in_flight = 1;
+        max_grid = 32;
+    }
     int grid = (total + 8 * in_flight - 1) / (8 * in_flight);
-    if (grid > kMaxGrid) grid = kMaxGrid;
+    if (grid > max_grid) grid = max_grid;
     if (grid < 1) return hipSuccess;
-    const auto kernel = in_flight == 2 ? gather_kernel<2> : in_flight == 3 ? gather_kernel<3> : gather_kernel<4>;
+    const auto kernel = in_flight == 1 ? gather_kernel<1> : in_flight == 2 ? gather_kernel<2> : in_flight == 3 ? gather_kernel<3> : gather_kernel<4>;
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk, total, idx,
                        (uint4*)slot, slot_idx);
     return hipGetLastError();
