@@ -24,16 +24,16 @@ WORKLOADS = {
     "M0": (1, 32, 32, 32768, 0, 2, 32, 256, 32),
     "c1": (1, 1, 1, 4096, 0, 2, 32, 64, 1),
     "c2": (1, 32, 32, 16384, 0, 2, 32, 256, 32),
-    "c3": (16, 32, 32, 2048, 0, 2, 32, 128, 1),
-    "c4": (4, 32, 8, 32768, 1, 2, 64, 512, 1),
+    "c3": (16, 32, 32, 2048, 0, 2, 32, 128, 4),
+    "c4": (4, 32, 8, 32768, 1, 2, 64, 512, 4),
     "c5": (1, 32, 8, 131072, 1, 1, 32, 1024, 32),
 }
 DESCR = {
     "M0": "7B shape at 32k context: B=1, 32 MHA heads, D=128, S=32768, fp16, 2-bit g32, k=256, 32 layers",
     "c1": "config 1: B=1, 1 head, S=4096, fp16, 2-bit g32, k=64, 1 layer",
     "c2": "config 2: B=1, 32 MHA heads, S=16384, fp16, 2-bit g32, k=256, 32 layers",
-    "c3": "config 3: B=16, 32 MHA heads, S=2048, fp16, 2-bit g32, k=128, 1 layer",
-    "c4": "config 4: B=4, 32/8 GQA heads, S=32768, bf16, 2-bit g64, k=512, 1 layer",
+    "c3": "config 3: B=16, 32 MHA heads, S=2048, fp16, 2-bit g32, k=128, 4 layers (512 MiB of host store each)",
+    "c4": "config 4: B=4, 32/8 GQA heads, S=32768, bf16, 2-bit g64, k=512, 4 layers (512 MiB of host store each)",
     "c5": "config 5: B=1, 32/8 GQA heads, S=131072, bf16, 1-bit g32, k=1024, 32 layers",
 }
 
