@@ -299,14 +299,16 @@ def test_selection_on_the_mixed_cache(Hq, Hkv, dtype, bits, g, form):
         binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_cache=2)
 
 
-def test_layers_alternating_two_side_streams():
+@pytest.mark.parametrize("async_select", [0, 1])
+def test_layers_alternating_two_side_streams(async_select):
     """Four layers stepped in turn, their gathers alternating between two side streams (two gathers are then in
-    flight at a time and the library paces them for a shared link).  Every layer holds the same cache and gets
-    the same queries, so every layer's selection and output must match the one oracle cache."""
+    flight at a time and the library paces them for a shared link), with ArgTopK on the caller's stream or on the
+    library's own.  Every layer holds the same cache and gets the same queries, so every layer's selection and
+    output must match the one oracle cache."""
     from oracle import oracle as orc
     from tests.harness import check_out, check_topk, to_dev
     layers, Hq, S, k, dtype, seed = 4, 3, 2300, 72, synth.FP16, 2900
-    sc = binding.SpeCache(layers, 1, Hq, Hq, 2, 32, 2432, k, dtype)
+    sc = binding.SpeCache(layers, 1, Hq, Hq, 2, 32, 2432, k, dtype, async_select=async_select)
     try:
         kb, vb = synth.make_kv(seed, 1, Hq, S, 128, dtype)
         oc = [orc.Cache(128, 2, 32, 64, dtype) for _ in range(Hq)]
@@ -319,7 +321,7 @@ def test_layers_alternating_two_side_streams():
         out = [torch.empty((1, Hq, 2, 128), dtype=torch.float32, device="cuda") for _ in range(layers)]
         prev = None
         sm = 1.0 / np.sqrt(128.0)
-        for t in range(4):
+        for t in range(6):
             q_bits = synth.make_queries(seed, 1, Hq, 128, dtype, n_rows=2, sub=t)
             ks_bits, vs_bits = synth.make_spec_kv(seed, 1, Hq, 128, dtype, sub=t)
             nk, nv = synth.make_step_kv(seed, t, 1, Hq, 128, dtype)
