@@ -83,6 +83,8 @@ def main():
                          "layer would hide")
     ap.add_argument("--topk", type=int, default=0,
                     help="override k, the number of prefetched pairs per (batch, KV head) (the k sweep of Section 4.4)")
+    ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
+                    help="override g, the quantisation group size (the residual becomes max(64, g))")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
@@ -132,7 +134,9 @@ def main():
         layers = args.layers
     if args.topk:
         k = args.topk
-    G, D, R = Hq // Hkv, 128, 64
+    if args.group:
+        g = args.group
+    G, D, R = Hq // Hkv, 128, max(64, g)
     total_steps = args.warmup + 4 * args.steps + 2
     max_seq = ((S + total_steps + 63) // 64 + 1) * 64
     seed = 1000
@@ -311,7 +315,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic" if not args.filler_mb else f"synthetic; EMULATED rest of the layer: {args.filler_mb} MB streamed per layer",
         "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
-                   "residual": R, "gather": not args.no_gather, "variant": args.variant,
+                   "residual": R, "group": g, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
                                    "main stream, gather of the next step's pairs on side streams",
                    "side_streams": len(side_list) if not args.serial_gather else 0,

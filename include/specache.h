@@ -61,8 +61,8 @@ typedef struct specache_config {
     int32_t n_kv_heads; /* Hkv >= 1                                                    */
     int32_t head_dim;   /* must be 128                                                 */
     int32_t bits;       /* 1 (Eq. 3) or 2 (Eq. 2)                                      */
-    int32_t group;      /* g: 32 or 64; keys grouped per channel over g tokens, values
-                           per token over g channels                                   */
+    int32_t group;      /* g: 32, 64 (the paper's) or 128; keys grouped per channel over
+                           g tokens, values per token over g channels                  */
     int32_t residual;   /* R: multiple of g, g <= R <= 256.  Tokens are appended one at
                            a time; when N - Nq reaches R the oldest g unquantised
                            tokens are quantised.  The paper uses 64.                   */

@@ -233,9 +233,11 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
             if constexpr (M == 4) {
                 const uint4 t4 = valid ? *reinterpret_cast<const uint4*>(vm_row + (size_t)(c0 + i) * 4) : make_uint4(0, 0, 0, 0);
                 meta[tt][0] = t4.x; meta[tt][1] = t4.y; meta[tt][2] = t4.z; meta[tt][3] = t4.w;
-            } else {
+            } else if constexpr (M == 2) {
                 const uint2 t2 = valid ? *reinterpret_cast<const uint2*>(vm_row + (size_t)(c0 + i) * 2) : make_uint2(0, 0);
                 meta[tt][0] = t2.x; meta[tt][1] = t2.y;
+            } else {
+                meta[tt][0] = valid ? vm_row[c0 + i] : 0u;
             }
         }
         // the first value codes of this thread, needed only after the softmax phase
@@ -342,9 +344,12 @@ __global__ __launch_bounds__(kThreads) void attend_partial_kernel(LayerView L, A
                     if constexpr (M == 4) {
                         *reinterpret_cast<float4*>(&zl[i * M]) = make_float4(zv[0], zv[1], zv[2], zv[3]);
                         *reinterpret_cast<float4*>(&sl[i * M]) = make_float4(scv[0], scv[1], scv[2], scv[3]);
-                    } else {
+                    } else if constexpr (M == 2) {
                         *reinterpret_cast<float2*>(&zl[i * M]) = make_float2(zv[0], zv[1]);
                         *reinterpret_cast<float2*>(&sl[i * M]) = make_float2(scv[0], scv[1]);
+                    } else {
+                        zl[i] = zv[0];
+                        sl[i] = scv[0];
                     }
                 }
             }
@@ -890,6 +895,8 @@ hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, i
     if (L.bits == 2 && L.group == 64) return launch2<2, 64>(L, A, n_rows, n_ex, out, stream);
     if (L.bits == 1 && L.group == 32) return launch2<1, 32>(L, A, n_rows, n_ex, out, stream);
     if (L.bits == 1 && L.group == 64) return launch2<1, 64>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 2 && L.group == 128) return launch2<2, 128>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 1 && L.group == 128) return launch2<1, 128>(L, A, n_rows, n_ex, out, stream);
     return hipErrorInvalidValue;
 }
 

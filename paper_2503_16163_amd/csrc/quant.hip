@@ -160,7 +160,9 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
             for (int b = 0; b < 4; ++b) kw[i] |= quantize_near<BITS>(kx[i][b], kz[b], krs[b], unsafe) << (8 * b);
         }
         if (unsafe) {
-#pragma unroll 1
+            // rolled where the token array still fits the registers that can be indexed at run time;
+            // beyond that a rolled loop would move the array to scratch memory for the fast path too
+#pragma unroll(NT > 8 ? NT : 1)
             for (int i = 0; i < NT; ++i) {
                 kw[i] = 0;
 #pragma unroll
@@ -197,9 +199,13 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
         mx = fmaxf(mx, dpp_f32<kDppXor2>(mx));
         mn = fminf(mn, dpp_f32<kDppHalfMirror>(mn));
         mx = fmaxf(mx, dpp_f32<kDppHalfMirror>(mx));
-        if constexpr (VL == 16) {
+        if constexpr (VL >= 16) {
             mn = fminf(mn, dpp_f32<kDppMirror>(mn));
             mx = fmaxf(mx, dpp_f32<kDppMirror>(mx));
+        }
+        if constexpr (VL == 32) {   // the two rows of 16 lanes of this half of the wave
+            mn = fminf(mn, __shfl_xor(mn, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
         }
         if (j % VL == 0) vm[e * M + j / VL] = narrow16<BF16>(mn) | (narrow16<BF16>(mx) << 16);
         float vs, vz;
@@ -226,20 +232,28 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
     __syncthreads();
 
     // ---- 16-byte pieces of the device layout ----
-    constexpr int kPieces = G * BITS;  // per operand; <= 128
-    if (tid < kPieces) {
+    constexpr int kPieces = G * BITS;  // per operand; <= 256
+    auto k_piece = [&](int id) {
         // K: [32-token sub-block][dword W][half of the lane's 8 tokens][quad lane]
-        const int kl = tid % 4, h2 = (tid / 4) % 2, W = (tid / 8) % NW, sb = tid / (8 * NW);
+        const int kl = id % 4, h2 = (id / 4) % 2, W = (id / 8) % NW, sb = id / (8 * NW);
         const int e = sb * 32 + kl * 8 + h2 * 4;
         const uint4 v = *reinterpret_cast<const uint4*>(&kd[W][e]);
         *reinterpret_cast<uint4*>(L.kc + (size_t)row * L.kc_stride + k_dword_offset<BITS>(t0 + e, W)) = v;
-    } else if (tid >= 128 && tid < 128 + kPieces) {
+    };
+    auto v_piece = [&](int id) {
         // V: [32-token block][half of 16 tokens][byte lane]
-        const int id = tid - 128;
         const int Lb = id % (16 * BITS), half = (id / (16 * BITS)) % 2, sb = id / (32 * BITS);
         const int e = sb * 32 + half * 16;
         const uint4 v = *reinterpret_cast<const uint4*>(&vb[Lb][e]);
         *reinterpret_cast<uint4*>(L.vc + (size_t)row * L.vc_stride + v_byte_offset<BITS>(t0 + e, Lb)) = v;
+    };
+    if constexpr (kPieces <= 128) {
+        if (tid < kPieces) k_piece(tid);
+        else if (tid >= 128 && tid < 128 + kPieces) v_piece(tid - 128);
+    } else {
+        static_assert(kPieces == kFlushThreads, "one K piece and one V piece per thread");
+        k_piece(tid);
+        v_piece(tid);
     }
 }
 
@@ -336,6 +350,8 @@ hipError_t launch_flush(const LayerView& L, const void* k_new, const void* v_new
     if (L.bits == 2 && L.group == 32) return flush_dispatch<2, 32>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 2 && L.group == 64) return flush_dispatch<2, 64>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 1 && L.group == 32) return flush_dispatch<1, 32>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
+    if (L.bits == 2 && L.group == 128) return flush_dispatch<2, 128>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
+    if (L.bits == 1 && L.group == 128) return flush_dispatch<1, 128>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 1 && L.group == 64) return flush_dispatch<1, 64>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     return hipErrorInvalidValue;
 }
@@ -355,6 +371,8 @@ hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t*
     if (L.bits == 2 && L.group == 32) return export_dispatch<2, 32>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 2 && L.group == 64) return export_dispatch<2, 64>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 1 && L.group == 32) return export_dispatch<1, 32>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
+    if (L.bits == 2 && L.group == 128) return export_dispatch<2, 128>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
+    if (L.bits == 1 && L.group == 128) return export_dispatch<1, 128>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 1 && L.group == 64) return export_dispatch<1, 64>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     return hipErrorInvalidValue;
 }

@@ -283,7 +283,7 @@ hipError_t launch2(const LayerView& L, const void* q, int n_rows, int Nq, float 
 hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits,
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream) {
     if (Nq <= 0) return hipSuccess;
-    if (L.group != 32 && L.group != 64) return hipErrorInvalidValue;
+    if (L.group != 32 && L.group != 64 && L.group != 128) return hipErrorInvalidValue;
     // two rows of one query head: the integer matrix cores take the contraction (it reads q 16 bytes at a time)
     if (score_uses_int8_matrix_cores(L.G, n_rows) && ((uintptr_t)q & 15) == 0)
         return launch_score_i8(L, q, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);

@@ -123,7 +123,7 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(8, 
     // ---- multipliers: lane (sub-group sgP, u) folds channel quads 2u and 2u + 1 of that sub-group
     const int sgP = lane >> 4, u = lane & 15;
     const int subP = sub0 + sgP < n_sub ? sub0 + sgP : n_sub - 1;
-    const int group_of_sub = L.group == 64 ? subP >> 1 : subP;  // two sub-groups share a 64-token group's metadata
+    const int group_of_sub = subP * kBlockTokens / L.group;     // the sub-groups of one token group share its metadata
     const uint32_t* km_p = L.km + (size_t)row * L.km_stride + (size_t)group_of_sub * kD + 2 * u;
     uint2 mt[4];                                               // (min, max) of channels 4 (2u + mq) + b, mq = .x/.y
 #pragma unroll
@@ -271,7 +271,7 @@ bool score_uses_int8_matrix_cores(int G, int n_rows) { return G == 1 && n_rows =
 
 hipError_t launch_score_i8(const LayerView& L, const void* q, int Nq, float sm_scale, float* logits,
                            size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream) {
-    if (L.G != 1 || (L.bits != 1 && L.bits != 2) || (L.group != 32 && L.group != 64) || Nq % L.group != 0)
+    if (L.G != 1 || (L.bits != 1 && L.bits != 2) || (L.group != 32 && L.group != 64 && L.group != 128) || Nq % L.group != 0)
         return hipErrorInvalidValue;
     const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kWaves);
 #define SPC_I8(B_, F_)                                                                                         \

@@ -214,7 +214,8 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
         return fail(nullptr, SPECACHE_EINVAL, "select_cache must be SPECACHE_SELECT_LOWBIT or SPECACHE_SELECT_MIXED");
     if (c.select_form != SPECACHE_SELECT_MAX_LOGIT && c.select_form != SPECACHE_SELECT_MAX_LOGPROB)
         return fail(nullptr, SPECACHE_EINVAL, "select_form must be SPECACHE_SELECT_MAX_LOGIT or SPECACHE_SELECT_MAX_LOGPROB");
-    if (c.group != 32 && c.group != 64) return fail(nullptr, SPECACHE_EINVAL, "group must be 32 or 64");
+    if (c.group != 32 && c.group != 64 && c.group != 128)
+        return fail(nullptr, SPECACHE_EINVAL, "group must be 32, 64 or 128");
     if (c.residual < c.group || c.residual % c.group || c.residual > 256)
         return fail(nullptr, SPECACHE_EINVAL, "residual must be a multiple of group in [group, 256]");
     if (c.max_seq < 64 || c.max_seq % 64) return fail(nullptr, SPECACHE_EINVAL, "max_seq must be a positive multiple of 64");

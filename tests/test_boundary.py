@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
 def test_plan_append_equals_token_by_token_simulation():
     import random
     rng = random.Random(5)
-    for R, g in [(64, 32), (64, 64), (96, 32), (128, 64), (256, 32)]:
+    for R, g in [(64, 32), (64, 64), (96, 32), (128, 64), (256, 32), (128, 128), (256, 128)]:
         for _ in range(500):
             r0, nq, n = rng.randrange(0, R), g * rng.randrange(0, 6), rng.randrange(0, 400)
             r, flushed = r0, 0

@@ -44,6 +44,10 @@ def test_config1_single_head():
     (2, 2, 2, 777, synth.FP16, 1, 64, 33, 128),      # 1-bit g64, R = 128, odd k
     (1, 4, 2, 900, synth.FP16, 2, 32, 64, 96),       # GQA 2:1, R = 96
     (1, 8, 1, 640, synth.BF16, 2, 32, 40, 64),       # GQA 8:1
+    (1, 2, 2, 3000, synth.FP16, 2, 128, 64, 128),    # g = R = 128, MHA (integer matrix-core scoring)
+    (1, 8, 2, 1500, synth.BF16, 1, 128, 50, 256),    # 1-bit g128, GQA 4:1, R = 256
+    (2, 4, 2, 1000, synth.FP16, 2, 128, 32, 128),    # g128, GQA 2:1
+    (1, 8, 1, 900, synth.BF16, 2, 128, 40, 256),     # g128, GQA 8:1
 ])
 def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
     from tests.harness import Case
@@ -51,13 +55,14 @@ def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
     print(stats)
 
 
-@pytest.mark.parametrize("dtype,bits,g", [(synth.FP16, 2, 32), (synth.BF16, 2, 64), (synth.FP16, 1, 32), (synth.BF16, 1, 64)])
+@pytest.mark.parametrize("dtype,bits,g", [(synth.FP16, 2, 32), (synth.BF16, 2, 64), (synth.FP16, 1, 32), (synth.BF16, 1, 64),
+                                          (synth.FP16, 2, 128), (synth.BF16, 1, 128)])
 def test_quantiser_on_rounding_boundaries(dtype, bits, g):
     """Inputs on a grid of half quantisation steps (and their 16-bit neighbours), constant groups and groups
     with tiny ranges: the quotients of Eq. 2 / Eq. 3 land exactly on, or one rounding away from, the
     round-half-up boundaries, where codes have to stay bit-exact."""
     from tests.harness import Case
-    c = Case(1, 2, 2, 1024, dtype, bits, g, 16, seed=4242)
+    c = Case(1, 2, 2, 1024, dtype, bits, g, 16, R=max(64, g), seed=4242)
     rng = np.random.default_rng(77)
     shape = c.k_bits.shape
     for name in ("k_bits", "v_bits"):
@@ -68,7 +73,7 @@ def test_quantiser_on_rounding_boundaries(dtype, bits, g):
         x = (m * 0.5) * np.exp2(e.astype(np.float64)) - (1.0 if bits == 1 else 0.0)
         b = synth.to_bits(x.astype(np.float32), dtype).astype(np.int32)
         b = b + rng.integers(-1, 2, size=shape) * (rng.random(shape) < 0.3)  # neighbours in the 16-bit format
-        b[:, :, 64:96] = b[:, :, 64:65]                                       # constant key groups: s = 0
+        b[:, :, 2 * g:3 * g] = b[:, :, 2 * g:2 * g + 1]                       # constant key groups: s = 0
         b[:, :, 200:210, :] = b[:, :, 200:210, :1]                            # constant value groups
         b = np.where((b & 0x7FFF) >= (0x7C00 if dtype == synth.FP16 else 0x7F80), 0, b)   # no inf / nan
         setattr(c, name, b.astype(np.uint16))
@@ -145,7 +150,7 @@ def test_integer_matrix_core_scoring_keeps_fp32_accuracy(dtype, bits, g, spread)
         c.close()
 
 
-@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128)])
+@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128), (2, 128, 128)])
 def test_long_decode_crosses_flushes(bits, g, R):
     """70 decode steps from a short prompt: the residual ring wraps and groups are flushed during decoding
     (every g steps), each step checked against the oracle, the whole quantised prefix and the offloaded rows
