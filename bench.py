@@ -89,9 +89,11 @@ def main():
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
     ap.add_argument("--side-streams", type=int, default=0,
-                    help="side streams the gathers alternate over by layer; 0 = 2 (two gathers share the link and cover "
-                         "each other's launch gaps) unless a fetched pair stands for 384 or more scored keys, where the "
-                         "gather has time to spare and one stream disturbs the other kernels less")
+                    help="side streams the gathers alternate over by layer; 0 = by the measured rule: with ArgTopK on the "
+                         "gather's stream 2, or 3 where a fetched pair stands for fewer than 192 scored keys (a third "
+                         "stream selects while two gathers share the link); otherwise 2 (two gathers share the link and "
+                         "cover each other's launch gaps), or 1 from 384 scored keys per pair on, where the gather has "
+                         "time to spare")
     ap.add_argument("--variant", default="speculative", choices=["speculative", "nonspec"],
                     help="nonspec: the non-speculative fetching of Section 4.4 (select on the current token, one query "
                          "row, gather on the main stream before attend): the whole link time is exposed")
@@ -107,11 +109,12 @@ def main():
     ap.add_argument("--select-cache", default="lowbit", choices=["lowbit", "mixed"],
                     help="which logits ArgTopK ranks: pure low-bit (default) or the mixed cache's (the staged positions "
                          "are scored with their 16-bit keys: one more small kernel per layer-step)")
-    ap.add_argument("--select-stream", default="auto", choices=["auto", "own", "main"],
-                    help="where ArgTopK runs: on a stream of the library's own beside the attention kernels "
-                         "(specache_config.async_select) or on the main stream; auto = own when several layers are "
-                         "stepped speculatively, main for the one-layer workloads and the non-speculative variant, where "
-                         "the extra stream calls cost more than they hide")
+    ap.add_argument("--select-stream", default="auto", choices=["auto", "own", "main", "gather"],
+                    help="where ArgTopK runs (specache_config.async_select): on the main stream, on a stream of the "
+                         "library's own beside the attention kernels, or on the gather's side stream ahead of the gather "
+                         "(the specache_score / specache_select_gather pair of calls); auto = main for one layer and for the "
+                         "non-speculative variant, else gather where a fetched pair stands for 96 or more scored keys "
+                         "(the step is bound by compute and by the issuing thread) and own below that (bound by the link)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -141,8 +144,17 @@ def main():
     max_seq = ((S + total_steps + 63) // 64 + 1) * 64
     seed = 1000
 
-    async_select = 1 if (args.select_stream == "own" or (args.select_stream == "auto" and layers > 1 and
-                                                          args.variant == "speculative")) else 0
+    # Where ArgTopK runs (measured rule).  keys_per_pair says how much scoring work stands against one fetched
+    # pair.  With much of it the step is bound by compute and by the issuing thread: ArgTopK then goes on the
+    # gather's stream, which needs the fewest ordering calls between streams.  With little of it the step is
+    # bound by the host link: ArgTopK on the library's own stream lets every gather start the moment its
+    # selection is done.  One layer, or the non-speculative variant: everything on the main stream.
+    keys_per_pair = G * S / k
+    side_gathers = args.variant == "speculative" and not args.serial_gather and not args.no_gather
+    if args.select_stream == "auto":
+        async_select = 0 if (layers == 1 or args.variant != "speculative") else (2 if side_gathers and keys_per_pair >= 96 else 1)
+    else:
+        async_select = {"main": 0, "own": 1, "gather": 2 if side_gathers else 1}[args.select_stream]
     sc = None
     while sc is None:
         try:
@@ -155,7 +167,12 @@ def main():
                 raise
             layers = max(1, layers // 2)   # the pinned host store did not fit: fewer layers
     main_s = torch.cuda.current_stream()
-    n_side = args.side_streams if args.side_streams > 0 else (1 if G * S >= 384 * k else 2)
+    if args.side_streams > 0:
+        n_side = args.side_streams
+    elif async_select == 2:
+        n_side = 3 if keys_per_pair < 192 else 2   # a third stream selects while two gathers share the link
+    else:
+        n_side = 1 if keys_per_pair >= 384 else 2
     side_list = [main_s] if args.serial_gather else [torch.cuda.Stream() for _ in range(n_side)]
 
     # ---- load the prompt: the same synthetic K/V tensor serves every layer ----------
@@ -200,28 +217,46 @@ def main():
     filler = torch.ones(args.filler_mb * (1 << 20) // 2, dtype=torch.float16, device="cuda") if args.filler_mb else None
     filler_out = torch.empty((), dtype=torch.float16, device="cuda")
 
+    # The step loop hands the library raw addresses and stream handles, as a serving loop would: building a
+    # tensor view per call costs the issuing thread several microseconds per layer, which shows once the
+    # step is short (small k).
+    q_p = [[q_all[p, L].data_ptr() for L in range(layers)] for p in range(nq_pool)]
+    q1_p = [[q1_all[p, L].data_ptr() for L in range(layers)] for p in range(nq_pool)]
+    k_p = [step_k[t].data_ptr() for t in range(total_steps)]
+    v_p = [step_v[t].data_ptr() for t in range(total_steps)]
+    idx_p = [[idx[L][b].data_ptr() for b in range(2)] for L in range(layers)]
+    out_p = [out[L].data_ptr() for L in range(layers)]
+    spec_k_p, spec_v_p = spec_k.data_ptr(), spec_v.data_ptr()
+    main_h = main_s.cuda_stream
+    side_h = [s.cuda_stream for s in side_list]
+
     def step_nonspec():
         t = state["t"]
         for L in range(layers):
-            q = q1_all[t % nq_pool, L]
-            sc.quantize_append(L, step_k[t], step_v[t], 1, main_s)
-            sc.score_topk(L, q, 1, idx[L][0], main_s)
-            sc.gather(L, idx[L][0], 0, main_s)
-            sc.attend(L, q, 1, None, None, 0, out[L], main_s)
+            q = q1_p[t % nq_pool][L]
+            sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
+            sc.score_topk(L, q, 1, idx_p[L][0], main_h)
+            sc.gather(L, idx_p[L][0], 0, main_h)
+            sc.attend(L, q, 1, None, None, 0, out_p[L], main_h)
         state["t"] = t + 1
 
     def step(gather=True):
         if args.variant == "nonspec":
             return step_nonspec()
         t = state["t"]
+        do_gather = gather and not args.no_gather
+        slot = (t % 2) if (t > 0 and not args.no_gather) else -1
         for L in range(layers):
-            q = q_all[t % nq_pool, L]
-            sc.quantize_append(L, step_k[t], step_v[t], 1, main_s)
-            sc.score_topk(L, q, 2, idx[L][t % 2], main_s)
-            if gather and not args.no_gather:
-                sc.gather(L, idx[L][t % 2], (t + 1) % 2, side_list[L % len(side_list)])
-            slot = (t % 2) if (t > 0 and not args.no_gather) else -1
-            sc.attend(L, q, 2, spec_k, spec_v, slot, out[L], main_s)
+            q = q_p[t % nq_pool][L]
+            sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
+            if async_select == 2:
+                sc.score(L, q, 2, main_h)
+                sc.select_gather(L, idx_p[L][t % 2], (t + 1) % 2 if do_gather else -1, side_h[L % len(side_h)])
+            else:
+                sc.score_topk(L, q, 2, idx_p[L][t % 2], main_h)
+                if do_gather:
+                    sc.gather(L, idx_p[L][t % 2], (t + 1) % 2, side_h[L % len(side_h)])
+            sc.attend(L, q, 2, spec_k_p, spec_v_p, slot, out_p[L], main_h)
             if filler is not None:
                 torch.sum(filler, dim=(0,), out=filler_out)
         state["t"] = t + 1
@@ -319,7 +354,7 @@ def main():
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
                                    "main stream, gather of the next step's pairs on side streams",
                    "side_streams": len(side_list) if not args.serial_gather else 0,
-                   "async_select": bool(async_select)},
+                   "async_select": int(async_select)},
         "score_topk_attend_us": breakdown["score_topk_attend"],
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "kernel_us_no_gather": per_kernel_ng,

@@ -94,8 +94,18 @@ typedef struct specache_config {
                            after the selection either way; on the caller's stream
                            topk_idx_out is complete only after the next
                            specache_score_topk call (of any layer), which waits for it,
-                           or after a device synchronise                               */
+                           or after a device synchronise.
+                           2 (SPECACHE_SELECT_STREAM_GATHER): ArgTopK runs on the gather's
+                           side stream, directly ahead of the gather: the caller uses
+                           specache_score + specache_select_gather in place of
+                           specache_score_topk + specache_gather.  Every layer then has a
+                           key array of its own (4 bytes per cached position and KV head)
+                           and a layer-step needs two event records and two event waits
+                           between the streams, against three and four with 1; each
+                           costs the issuing thread several microseconds                */
 } specache_config;
+
+enum { SPECACHE_SELECT_STREAM_CALLER = 0, SPECACHE_SELECT_STREAM_OWN = 1, SPECACHE_SELECT_STREAM_GATHER = 2 };
 
 typedef struct specache_ctx specache_ctx;
 
@@ -173,6 +183,27 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
  * Errors: EINVAL (slot not 0/1, null idx, bad layer).
  */
 int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_t slot, void* side_stream);
+
+/*
+ * The same two steps split at the other seam (contexts created with async_select =
+ * SPECACHE_SELECT_STREAM_GATHER only; ESTATE otherwise).
+ * specache_score: the scoring pass of specache_score_topk alone, on `stream`: the
+ * logits for the following specache_attend and the layer's selection keys.
+ * specache_select_gather: ArgTopK of those keys (Appendix A "Decoding":
+ * K_{t+1} = ArgTopK(A_{1,:})) followed by Pre-fetch(C_K) of the selected pairs into
+ * staging slot `slot`, both on side_stream, ordered after the layer's last
+ * specache_score and after the last specache_attend that read the slot.
+ * topk_idx_out (device int32 [B, Hkv, k], format as in specache_score_topk) is written
+ * on side_stream; it is complete when the gather is (a specache_attend on that slot
+ * follows both).  slot = -1: the selection alone, nothing is fetched (topk_idx_out is
+ * then complete for work enqueued on side_stream after the call, or after a device
+ * synchronise).  The next specache_score of the layer orders itself after this
+ * selection.  Arguments, ownership and slot semantics as in specache_score_topk and
+ * specache_gather.
+ * Errors: EINVAL, ESTATE (wrong mode; select_gather without a specache_score before it).
+ */
+int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream);
+int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream);
 
 /*
  * Mixed attention, Eq. 1: O = Attn([T_t, T'_{t+1}], C' u C_K).

@@ -71,6 +71,7 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
     constexpr int NW = 4 * BITS;     // K code dwords per token
     constexpr int KL = 32 / BITS / 4;  // lanes that share one K code dword
     constexpr int VL = G / 4;        // lanes of one value group
+    constexpr int kExactUnroll = NT > 8 ? NT : 1;   // see the exact-division path of the keys
     __shared__ float kmn[8][kD];
     __shared__ float kmx[8][kD];
     __shared__ __align__(16) uint32_t kd[NW][G];
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kFlushThreads) void flush_kernel(LayerView L, const
         if (unsafe) {
             // rolled where the token array still fits the registers that can be indexed at run time;
             // beyond that a rolled loop would move the array to scratch memory for the fast path too
-#pragma unroll(NT > 8 ? NT : 1)
+#pragma unroll kExactUnroll
             for (int i = 0; i < NT; ++i) {
                 kw[i] = 0;
 #pragma unroll

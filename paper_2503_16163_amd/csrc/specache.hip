@@ -51,6 +51,19 @@ struct Layer {
     uint64_t idx_ready_seq = 0;
     const int32_t* last_gather_idx = nullptr;
     int last_gather_slot = -1;
+    // ArgTopK on the gather's stream (specache_score + specache_select_gather): the layer has a key
+    // array of its own, which the selection reads on the side stream while the caller's stream goes
+    // on to other layers.  The next scoring pass of the layer waits for the gather that followed
+    // that selection; the attend after it then needs no wait of its own for the same slot.
+    uint32_t* keys = nullptr;            // [rows][logit_stride]
+    bool keys_valid = false;
+    int keys_Nq = 0;
+    int keys_reader_slot = -1;           // slot of the select_gather that read `keys` last
+    bool gathered_waited_set[2] = {false, false};
+    hipStream_t gathered_waited[2] = {nullptr, nullptr};   // stream that has already waited for gathered[s]
+    hipEvent_t selected = nullptr;       // a selection without a gather behind it (select_gather with slot -1)
+    bool selected_pending = false;
+    hipStream_t selected_stream = nullptr;
 };
 
 thread_local std::string g_create_error;
@@ -78,6 +91,12 @@ struct specache_ctx {
     hipStream_t select_stream = nullptr;
     hipEvent_t scored = nullptr;            // scoring pass done (recorded on the caller's stream)
     hipEvent_t last_select = nullptr;       // idx_ready of the most recent selection: it has read ctx->keys
+    // selections on the gather's stream: those of two side streams may overlap, so the candidate
+    // arrays of the two-launch ArgTopK exist twice, each remembering its last user
+    bool select_on_gather = false;
+    struct SelectScratch { TopkScratch s{}; bool used = false; hipStream_t stream = nullptr; hipEvent_t done = nullptr; };
+    SelectScratch select_scratch[2];
+    int select_scratch_next = 0;
     std::string err;
     // optional per-kernel timing: (start, stop) event pairs recorded around each launch
     bool timing = false;
@@ -168,7 +187,10 @@ void free_all(specache_ctx* ctx) {
             if (L.attended[s]) (void)hipEventDestroy(L.attended[s]);
         }
         if (L.idx_ready) (void)hipEventDestroy(L.idx_ready);
+        if (L.selected) (void)hipEventDestroy(L.selected);
+        (void)hipFree(L.keys);
     }
+    for (auto& ss : ctx->select_scratch) { (void)hipFree(ss.s.cand_keys); (void)hipFree(ss.s.cand_idx); }
     for (auto& sp : ctx->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
     (void)hipFree(ctx->logits);
@@ -180,6 +202,66 @@ void free_all(specache_ctx* ctx) {
     (void)hipFree(ctx->scratch.part_ml);
     (void)hipFree(ctx->topk_scratch.cand_keys);
     (void)hipFree(ctx->topk_scratch.cand_idx);
+}
+
+// The scoring pass of one layer on stream st: low-bit logits of every query row, selection keys of
+// the last row, and the optional rewrites of those keys (mixed-cache selection, log-probability form).
+int score_phase(specache_ctx* ctx, Layer& L, const void* q, int n_rows, uint32_t* keys, hipStream_t st) {
+    if (L.Nq > 0) {
+        TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
+        SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, keys,
+                                  ctx->logit_stride, st));
+        // selection on the mixed cache: the positions staged by the layer's last gather are scored with
+        // their 16-bit keys (that slot is the one the coming attend reads; the next gather into it
+        // waits for this stream's next selection event, so it cannot overtake the patch)
+        if (ctx->cfg.select_cache == SPECACHE_SELECT_MIXED && L.last_gather_slot >= 0) {
+            const int sl = L.last_gather_slot;
+            if (L.gather_stream[sl] != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[sl], 0));
+            SPC_HIP(ctx, launch_patch_staged(L.view, q, n_rows, L.Nq, ctx->sm_scale, L.slot[sl], L.slot_idx[sl], ctx->logits,
+                                             ctx->logit_stride, keys, ctx->logit_stride, st));
+        }
+        // several query heads per KV head and the log-probability form: the keys are rewritten from
+        // the logits shifted by every head's log-sum-exp (one head: same order, nothing to do)
+        if (ctx->cfg.select_form == SPECACHE_SELECT_MAX_LOGPROB && L.view.G > 1)
+            SPC_HIP(ctx, launch_select_logprob(L.view, n_rows, L.Nq, ctx->logits, ctx->logit_stride, ctx->lse, keys,
+                                               ctx->logit_stride, st));
+    }
+    return SPECACHE_OK;
+}
+
+// Orders a gather into `slot` on stream st after the attend that read the slot last.
+int order_gather_after_attend(specache_ctx* ctx, Layer& L, int slot, hipStream_t st) {
+    if (L.attend_seq[slot] != 0 && L.attend_stream[slot] != st) {
+        const bool behind_idx_ready = L.idx_ready_recorded && L.attend_stream[slot] == L.select_origin_stream &&
+                                      L.attend_seq[slot] < L.idx_ready_seq;
+        if (!L.attended_recorded[slot] && !behind_idx_ready) {
+            // a second gather into the slot without a new score_topk in between: record now, on the
+            // attend's stream, which orders this gather after everything enqueued there so far
+            SPC_HIP(ctx, hipEventRecord(L.attended[slot], L.attend_stream[slot]));
+            L.attended_recorded[slot] = true;
+        }
+        if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
+    }
+    return SPECACHE_OK;
+}
+
+// Launches the gather of `idx` into `slot` on st and records its completion.
+int gather_phase(specache_ctx* ctx, Layer& L, int Nq, const int32_t* idx, int slot, hipStream_t st) {
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
+        // a caller that alternates side streams has two gathers on the link at a time
+        const bool link_shared = ctx->last_gather_stream_set && ctx->last_gather_stream != st;
+        SPC_HIP(ctx, launch_gather(L.view, Nq, idx, L.slot[slot], L.slot_idx[slot], link_shared, st));
+        ctx->last_gather_stream = st;
+        ctx->last_gather_stream_set = true;
+    }
+    SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
+    L.gather_stream[slot] = st;
+    L.gathered_waited_set[slot] = false;
+    L.slot_filled[slot] = true;
+    L.last_gather_idx = idx;
+    L.last_gather_slot = slot;
+    return SPECACHE_OK;
 }
 
 }  // namespace
@@ -209,7 +291,7 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
     if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
         return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
-    if (c.async_select != 0 && c.async_select != 1) return fail(nullptr, SPECACHE_EINVAL, "async_select must be 0 or 1");
+    if (c.async_select < 0 || c.async_select > 2) return fail(nullptr, SPECACHE_EINVAL, "async_select must be 0, 1 or 2");
     if (c.select_cache != SPECACHE_SELECT_LOWBIT && c.select_cache != SPECACHE_SELECT_MIXED)
         return fail(nullptr, SPECACHE_EINVAL, "select_cache must be SPECACHE_SELECT_LOWBIT or SPECACHE_SELECT_MIXED");
     if (c.select_form != SPECACHE_SELECT_MAX_LOGIT && c.select_form != SPECACHE_SELECT_MAX_LOGPROB)
@@ -286,7 +368,22 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
         }
         SPC_ALLOC(hipEventCreateWithFlags(&L.idx_ready, kOrderEventFlags));
     }
-    ctx->async_select = c.async_select != 0;
+    ctx->async_select = c.async_select == SPECACHE_SELECT_STREAM_OWN;
+    ctx->select_on_gather = c.async_select == SPECACHE_SELECT_STREAM_GATHER;
+    if (ctx->select_on_gather) {
+        for (Layer& L : ctx->layers) {
+            SPC_ALLOC(hipMalloc((void**)&L.keys, (size_t)rows * cap * 4));
+            SPC_ALLOC(hipEventCreateWithFlags(&L.selected, kOrderEventFlags));
+        }
+        const int parts = topk_parts((int)cap, c.topk);
+        for (auto& ss : ctx->select_scratch) {
+            ss.s.max_parts = parts;
+            if (parts > 1) {
+                SPC_ALLOC(hipMalloc((void**)&ss.s.cand_keys, (size_t)rows * parts * c.topk * 4));
+                SPC_ALLOC(hipMalloc((void**)&ss.s.cand_idx, (size_t)rows * parts * c.topk * 4));
+            }
+        }
+    }
     if (ctx->async_select) {
         SPC_ALLOC(hipStreamCreateWithFlags(&ctx->select_stream, hipStreamNonBlocking));
         SPC_ALLOC(hipEventCreateWithFlags(&ctx->scored, kOrderEventFlags));
@@ -373,25 +470,7 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
         SPC_HIP(ctx, hipStreamWaitEvent(tk, L.gathered[L.last_gather_slot], 0));
     // the key array is shared by all layers: the previous selection, running aside, must have read it
     if (ctx->async_select && ctx->last_select) SPC_HIP(ctx, hipStreamWaitEvent(st, ctx->last_select, 0));
-    if (L.Nq > 0) {
-        TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
-        SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, ctx->keys,
-                                  ctx->logit_stride, st));
-        // selection on the mixed cache: the positions staged by the layer's last gather are scored with
-        // their 16-bit keys (that slot is the one the coming attend reads; the next gather into it
-        // waits for this stream's next selection event, so it cannot overtake the patch)
-        if (ctx->cfg.select_cache == SPECACHE_SELECT_MIXED && L.last_gather_slot >= 0) {
-            const int sl = L.last_gather_slot;
-            if (L.gather_stream[sl] != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[sl], 0));
-            SPC_HIP(ctx, launch_patch_staged(L.view, q, n_rows, L.Nq, ctx->sm_scale, L.slot[sl], L.slot_idx[sl], ctx->logits,
-                                             ctx->logit_stride, ctx->keys, ctx->logit_stride, st));
-        }
-        // several query heads per KV head and the log-probability form: the keys are rewritten from
-        // the logits shifted by every head's log-sum-exp (one head: same order, nothing to do)
-        if (ctx->cfg.select_form == SPECACHE_SELECT_MAX_LOGPROB && L.view.G > 1)
-            SPC_HIP(ctx, launch_select_logprob(L.view, n_rows, L.Nq, ctx->logits, ctx->logit_stride, ctx->lse, ctx->keys,
-                                               ctx->logit_stride, st));
-    }
+    if (int rc = score_phase(ctx, L, q, n_rows, ctx->keys, st)) return rc;
     if (ctx->async_select) {
         SPC_HIP(ctx, hipEventRecord(ctx->scored, st));
         SPC_HIP(ctx, hipStreamWaitEvent(tk, ctx->scored, 0));
@@ -414,6 +493,91 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     return SPECACHE_OK;
 }
 
+int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!ctx->select_on_gather) return fail(ctx, SPECACHE_ESTATE, "specache_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    if (!q) return fail(ctx, SPECACHE_EINVAL, "null q");
+    if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    Layer& L = ctx->layers[layer];
+    hipStream_t st = (hipStream_t)stream;
+    // the layer's previous selection read L.keys on the stream of the gather that followed it
+    if (L.keys_reader_slot >= 0) {
+        const int sl = L.keys_reader_slot;
+        if (L.gather_stream[sl] != st && !(L.gathered_waited_set[sl] && L.gathered_waited[sl] == st)) {
+            SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[sl], 0));
+            L.gathered_waited[sl] = st;
+            L.gathered_waited_set[sl] = true;
+        }
+        L.keys_reader_slot = -1;
+    }
+    if (L.selected_pending) {
+        if (L.selected_stream != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.selected, 0));
+        L.selected_pending = false;
+    }
+    if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) return rc;
+    // "scored": what the selection waits for, and what orders a gather after the attends enqueued so far
+    SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
+    L.idx_ready_recorded = true;
+    L.idx_ready_stream = st;
+    L.select_origin_stream = st;
+    L.idx_ready_seq = ++ctx->seq;
+    L.keys_valid = true;
+    L.keys_Nq = L.Nq;
+    ctx->scored_layer = layer;
+    ctx->scored_rows = n_rows;
+    ctx->scored_N = L.N;
+    ctx->scored_Nq = L.Nq;
+    return SPECACHE_OK;
+}
+
+int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!ctx->select_on_gather)
+        return fail(ctx, SPECACHE_ESTATE, "specache_select_gather needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    if (!topk_idx_out) return fail(ctx, SPECACHE_EINVAL, "null topk_idx_out");
+    if (slot < -1 || slot > 1) return fail(ctx, SPECACHE_EINVAL, "slot must be -1, 0 or 1");
+    Layer& L = ctx->layers[layer];
+    if (!L.keys_valid) return fail(ctx, SPECACHE_ESTATE, "specache_select_gather must follow specache_score of the layer");
+    hipStream_t st = (hipStream_t)side_stream;
+    if (st != L.idx_ready_stream) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
+    // a gather on another stream that still reads this index buffer must finish before it is overwritten
+    if (L.last_gather_idx == topk_idx_out && L.last_gather_slot >= 0 && L.gather_stream[L.last_gather_slot] != st)
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
+    if (slot >= 0)
+        if (int rc = order_gather_after_attend(ctx, L, slot, st)) return rc;
+    specache_ctx::SelectScratch* ss = nullptr;
+    if (ctx->select_scratch[0].s.max_parts > 1) {
+        // the candidate arrays last used on this stream, else the set whose turn it is (after its last user)
+        for (auto& c : ctx->select_scratch)
+            if (c.used && c.stream == st) ss = &c;
+        if (!ss) {
+            ss = &ctx->select_scratch[ctx->select_scratch_next];
+            ctx->select_scratch_next ^= 1;
+            if (ss->used) SPC_HIP(ctx, hipStreamWaitEvent(st, ss->done, 0));
+        }
+    }
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_TOPK, /*kernel_events=*/true);
+        SPC_HIP(ctx, launch_topk(L.view.rows, L.keys_Nq, ctx->cfg.topk, L.keys, ctx->logit_stride, topk_idx_out,
+                                 ss ? ss->s : ctx->select_scratch[0].s, st));
+    }
+    if (slot >= 0) {
+        if (int rc = gather_phase(ctx, L, L.keys_Nq, topk_idx_out, slot, st)) return rc;
+        L.keys_reader_slot = slot;
+    } else {
+        // selection only: an event of its own tells the layer's next scoring pass that the keys were read
+        SPC_HIP(ctx, hipEventRecord(L.selected, st));
+        L.selected_pending = true;
+        L.selected_stream = st;
+    }
+    if (ss) {
+        ss->used = true;
+        ss->stream = st;
+        ss->done = slot >= 0 ? L.gathered[slot] : L.selected;   // recorded behind the selection on this stream
+    }
+    return SPECACHE_OK;
+}
+
 int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_t slot, void* side_stream) {
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!idx) return fail(ctx, SPECACHE_EINVAL, "null idx");
@@ -421,30 +585,8 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)side_stream;
     if (L.idx_ready_recorded && st != L.idx_ready_stream) SPC_HIP(ctx, hipStreamWaitEvent(st, L.idx_ready, 0));
-    if (L.attend_seq[slot] != 0 && L.attend_stream[slot] != st) {
-        const bool behind_idx_ready = L.idx_ready_recorded && L.attend_stream[slot] == L.select_origin_stream &&
-                                      L.attend_seq[slot] < L.idx_ready_seq;
-        if (!L.attended_recorded[slot] && !behind_idx_ready) {
-            // a second gather into the slot without a new score_topk in between: record now, on the
-            // attend's stream, which orders this gather after everything enqueued there so far
-            SPC_HIP(ctx, hipEventRecord(L.attended[slot], L.attend_stream[slot]));
-            L.attended_recorded[slot] = true;
-        }
-        if (L.attended_recorded[slot]) SPC_HIP(ctx, hipStreamWaitEvent(st, L.attended[slot], 0));
-    }
-    {
-        TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
-        // a caller that alternates side streams has two gathers on the link at a time
-        const bool link_shared = ctx->last_gather_stream_set && ctx->last_gather_stream != st;
-        SPC_HIP(ctx, launch_gather(L.view, L.Nq, idx, L.slot[slot], L.slot_idx[slot], link_shared, st));
-        ctx->last_gather_stream = st;
-        ctx->last_gather_stream_set = true;
-    }
-    SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
-    L.gather_stream[slot] = st;
-    L.slot_filled[slot] = true;
-    L.last_gather_idx = idx;
-    L.last_gather_slot = slot;
+    if (int rc = order_gather_after_attend(ctx, L, slot, st)) return rc;
+    if (int rc = gather_phase(ctx, L, L.Nq, idx, slot, st)) return rc;
     return SPECACHE_OK;
 }
 
@@ -461,7 +603,8 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
     if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
     hipStream_t st = (hipStream_t)stream;
-    if (slot >= 0 && L.gather_stream[slot] != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
+    if (slot >= 0 && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
     {
         TimedLaunch t(ctx, st, SPECACHE_K_ATTEND);
         SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,

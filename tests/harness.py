@@ -70,6 +70,7 @@ class Case:
         self.sample = sample if sample is not None else [(b, h) for b in range(B) for h in range(Hkv)]
         cap = max_seq or ((S + 64 + 63) // 64) * 64
         self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
+        self.async_select = async_select
         self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
                                    select_form=select_form, select_cache=select_cache, async_select=async_select)
@@ -150,9 +151,13 @@ class Case:
         ks, vs = (to_dev(ks_bits, self.dtype), to_dev(vs_bits, self.dtype)) if use_spec else (None, None)
         idx = self.idx[t % 2]
         main = torch.cuda.current_stream()
-        self.sc.score_topk(0, q, nr, idx, main)
-        if do_gather:
-            self.sc.gather(0, idx, (t + 1) % 2, self.side)
+        if self.async_select == 2:   # ArgTopK on the gather's stream: the other pair of calls
+            self.sc.score(0, q, nr, main)
+            self.sc.select_gather(0, idx, (t + 1) % 2 if do_gather else -1, self.side)
+        else:
+            self.sc.score_topk(0, q, nr, idx, main)
+            if do_gather:
+                self.sc.gather(0, idx, (t + 1) % 2, self.side)
         out = torch.empty((self.B, self.Hq, nr, self.D), dtype=torch.float32, device="cuda")
         slot = (t % 2) if (t > 0 and do_gather) else -1
         self.sc.attend(0, q, nr, ks, vs, slot, out, main)

@@ -304,12 +304,14 @@ def test_selection_on_the_mixed_cache(Hq, Hkv, dtype, bits, g, form):
         binding.SpeCache(1, 1, 1, 1, 2, 32, 256, 8, synth.FP16, select_cache=2)
 
 
-@pytest.mark.parametrize("async_select", [0, 1])
+@pytest.mark.parametrize("async_select", [0, 1, 2])
 def test_layers_alternating_two_side_streams(async_select):
     """Four layers stepped in turn, their gathers alternating between two side streams (two gathers are then in
-    flight at a time and the library paces them for a shared link), with ArgTopK on the caller's stream or on the
-    library's own.  Every layer holds the same cache and gets the same queries, so every layer's selection and
-    output must match the one oracle cache."""
+    flight at a time and the library paces them for a shared link), with ArgTopK on the caller's stream, on the
+    library's own, or on the gather's (the score / select_gather pair of calls).  Two steps are enqueued back to
+    back before the host looks at anything, so that the library's own ordering carries the dependencies between
+    them.  Every layer holds the same cache and gets the same queries, so every layer's selection and output must
+    match the one oracle cache."""
     from oracle import oracle as orc
     from tests.harness import check_out, check_topk, to_dev
     layers, Hq, S, k, dtype, seed = 4, 3, 2300, 72, synth.FP16, 2900
@@ -323,9 +325,10 @@ def test_layers_alternating_two_side_streams(async_select):
         for L in range(layers):
             sc.quantize_append(L, to_dev(kb, dtype), to_dev(vb, dtype), S)
         idx = [[torch.full((1, Hq, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)] for _ in range(layers)]
-        out = [torch.empty((1, Hq, 2, 128), dtype=torch.float32, device="cuda") for _ in range(layers)]
+        out = [[torch.empty((1, Hq, 2, 128), dtype=torch.float32, device="cuda") for _ in range(2)] for _ in range(layers)]
         prev = None
         sm = 1.0 / np.sqrt(128.0)
+        pending = []
         for t in range(6):
             q_bits = synth.make_queries(seed, 1, Hq, 128, dtype, n_rows=2, sub=t)
             ks_bits, vs_bits = synth.make_spec_kv(seed, 1, Hq, 128, dtype, sub=t)
@@ -334,24 +337,33 @@ def test_layers_alternating_two_side_streams(async_select):
             nkd, nvd = to_dev(nk, dtype), to_dev(nv, dtype)
             for L in range(layers):
                 sc.quantize_append(L, nkd, nvd, 1, main)
-                sc.score_topk(L, q, 2, idx[L][t % 2], main)
-                sc.gather(L, idx[L][t % 2], (t + 1) % 2, sides[L % 2])
-                sc.attend(L, q, 2, ks, vs, (t % 2) if t > 0 else -1, out[L], main)
+                if async_select == 2:
+                    sc.score(L, q, 2, main)
+                    sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, sides[L % 2])
+                else:
+                    sc.score_topk(L, q, 2, idx[L][t % 2], main)
+                    sc.gather(L, idx[L][t % 2], (t + 1) % 2, sides[L % 2])
+                sc.attend(L, q, 2, ks, vs, (t % 2) if t > 0 else -1, out[L][t % 2], main)
+            pending.append((t, q_bits, ks_bits, vs_bits, nk, nv, (q, ks, vs, nkd, nvd)))
+            if t % 2 == 0:
+                continue
             torch.cuda.synchronize()
-            for h in range(Hq):
-                oc[h].append(nk[0, h], nv[0, h])
-            cur = [idx[L][t % 2].cpu().numpy() for L in range(layers)]
-            for h in range(Hq):
-                qh = q_bits[0, h:h + 1]
-                _, sigma = oc[h].scores(qh, sm)
-                ref = oc[h].attend(qh, sm, P=prev[0][0, h] if prev is not None else None, k_spec=ks_bits[0, h, 0],
-                                   v_spec=vs_bits[0, h, 0])
-                for L in range(layers):
-                    check_topk(sigma, cur[L][0, h], k, what=f"layer {L} head {h} step {t}")
-                    check_out(out[L].cpu().numpy()[0, h:h + 1], ref, what=f"layer {L} head {h} step {t}")
-            for L in range(1, layers):
-                assert np.array_equal(cur[L], cur[0])
-            prev = cur
+            for (tt, q_bits, ks_bits, vs_bits, nk, nv, _) in pending:
+                for h in range(Hq):
+                    oc[h].append(nk[0, h], nv[0, h])
+                cur = [idx[L][tt % 2].cpu().numpy() for L in range(layers)]
+                for h in range(Hq):
+                    qh = q_bits[0, h:h + 1]
+                    _, sigma = oc[h].scores(qh, sm)
+                    ref = oc[h].attend(qh, sm, P=prev[0][0, h] if prev is not None else None, k_spec=ks_bits[0, h, 0],
+                                       v_spec=vs_bits[0, h, 0])
+                    for L in range(layers):
+                        check_topk(sigma, cur[L][0, h], k, what=f"layer {L} head {h} step {tt}")
+                        check_out(out[L][tt % 2].cpu().numpy()[0, h:h + 1], ref, what=f"layer {L} head {h} step {tt}")
+                for L in range(1, layers):
+                    assert np.array_equal(cur[L], cur[0])
+                prev = cur
+            pending = []
     finally:
         torch.cuda.synchronize()
         sc.close()
@@ -384,6 +396,72 @@ def test_selection_on_a_stream_of_its_own(Hq, Hkv, dtype, bits, g, form, mixed):
             c.nonspec_step()
     finally:
         c.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g,form,mixed", [(2, 2, synth.FP16, 2, 32, 0, 0), (8, 2, synth.BF16, 1, 32, 1, 1),
+                                                             (4, 2, synth.FP16, 2, 128, 0, 1)])
+def test_selection_on_the_gathers_stream(Hq, Hkv, dtype, bits, g, form, mixed):
+    """async_select = 2: the caller scores with specache_score and hands ArgTopK and the gather to the side stream
+    in one call (specache_select_gather).  Same results as the other two arrangements across flushes; the
+    non-speculative flow (gather on the main stream) still goes through specache_score_topk in such a context."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 1700, dtype, bits, g, 48, R=max(64, g), seed=3100 + Hq + g, select_form=form, select_cache=mixed,
+             async_select=2)
+    try:
+        c.load()
+        for t in range(40):
+            c.append_token(t)
+            if t % 8 == 0 or t > 36:
+                c.decode_step()
+            else:
+                c.decode_step(check_logits=False)
+        c.check_quantized()
+    finally:
+        c.close()
+    c = Case(1, 2, 2, 900, synth.FP16, 2, 32, 24, seed=3150, n_rows=1, async_select=2)
+    try:
+        c.load()
+        for t in range(3):
+            c.append_token(t)
+            c.nonspec_step()
+    finally:
+        c.close()
+
+
+def test_two_launch_selection_on_two_gather_streams():
+    """async_select = 2 with rows long enough for the two-launch ArgTopK (> 65536 keys): the selections of
+    consecutive layers run on different side streams and may overlap, each with candidate arrays of its own.
+    Both layers hold the same cache, so both must select what the oracle does."""
+    from oracle import oracle as orc
+    from tests.harness import check_topk, to_dev
+    S, k, dtype, seed, layers = 70000, 500, synth.FP16, 3200, 3
+    sc = binding.SpeCache(layers, 1, 1, 1, 2, 32, 70144, k, dtype, async_select=2)
+    try:
+        kb, vb = synth.make_kv(seed, 1, 1, S, 128, dtype)
+        oc = orc.Cache(128, 2, 32, 64, dtype)
+        oc.append(kb[0, 0], vb[0, 0])
+        main, sides = torch.cuda.current_stream(), [torch.cuda.Stream(), torch.cuda.Stream()]
+        kd, vd = to_dev(kb, dtype), to_dev(vb, dtype)
+        for L in range(layers):
+            sc.quantize_append(L, kd, vd, S)
+        assert sc.counts(0)[1] > 65536
+        idx = [[torch.full((1, 1, k), -7, dtype=torch.int32, device="cuda") for _ in range(2)] for _ in range(layers)]
+        out = torch.empty((1, 1, 2, 128), dtype=torch.float32, device="cuda")
+        sm = 1.0 / np.sqrt(128.0)
+        for t in range(3):
+            q_bits = synth.make_queries(seed, 1, 1, 128, dtype, n_rows=2, sub=t)
+            q = to_dev(q_bits, dtype)
+            for L in range(layers):
+                sc.score(L, q, 2, main)
+                sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, sides[L % 2])
+                sc.attend(L, q, 2, None, None, (t % 2) if t > 0 else -1, out, main)
+            torch.cuda.synchronize()
+            _, sigma = oc.scores(q_bits[0, 0:1], sm)
+            for L in range(layers):
+                check_topk(sigma, idx[L][t % 2].cpu().numpy()[0, 0], k, what=f"layer {L} step {t}")
+    finally:
+        torch.cuda.synchronize()
+        sc.close()
 
 
 def test_short_cache_edges():
@@ -449,6 +527,8 @@ def test_error_paths():
             (lambda: sc.score_topk(0, q, 3, idx), binding.EINVAL),
             (lambda: sc.gather(0, idx, 2), binding.EINVAL),
             (lambda: sc.attend(0, q, 2, None, None, -1, out), binding.ESTATE),   # nothing scored
+            (lambda: sc.score(0, q, 2), binding.ESTATE),                         # context not created for that pair of calls
+            (lambda: sc.select_gather(0, idx, 0), binding.ESTATE),
         ]:
             with pytest.raises(binding.SpeCacheError) as ei:
                 fn()
@@ -464,6 +544,14 @@ def test_error_paths():
         sc.attend(0, q, 2, None, None, -1, out)
         torch.cuda.synchronize()
         assert sc.counts(0) == (100, 64) and sc.counts(1) == (0, 0)
+    finally:
+        sc.close()
+    sc = binding.SpeCache(1, 1, 2, 2, 2, 32, 256, 16, synth.FP16, async_select=2)
+    try:
+        idx = torch.zeros((1, 2, 16), dtype=torch.int32, device="cuda")
+        with pytest.raises(binding.SpeCacheError) as ei:
+            sc.select_gather(0, idx, 0)                                          # nothing scored yet
+        assert ei.value.code == binding.ESTATE
     finally:
         sc.close()
     for kwargs in [dict(bits=3), dict(group=48), dict(residual=48), dict(max_seq=100), dict(topk=0), dict(head_dim=64),
