@@ -247,6 +247,9 @@ int order_gather_after_attend(specache_ctx* ctx, Layer& L, int slot, hipStream_t
 
 // Launches the gather of `idx` into `slot` on st and records its completion.
 int gather_phase(specache_ctx* ctx, Layer& L, int Nq, const int32_t* idx, int slot, hipStream_t st) {
+    // the slot's previous gather, if it ran on another stream that this one has not waited for
+    if (L.slot_filled[slot] && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
     {
         TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
         // a caller that alternates side streams has two gathers on the link at a time
@@ -545,6 +548,11 @@ int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_o
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.last_gather_slot], 0));
     if (slot >= 0)
         if (int rc = order_gather_after_attend(ctx, L, slot, st)) return rc;
+    // an earlier selection of the same keys on another stream: the next scoring pass waits for the
+    // latest selection only, so this one goes behind it
+    if (L.keys_reader_slot >= 0 && L.gather_stream[L.keys_reader_slot] != st)
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[L.keys_reader_slot], 0));
+    if (L.selected_pending && L.selected_stream != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.selected, 0));
     specache_ctx::SelectScratch* ss = nullptr;
     if (ctx->select_scratch[0].s.max_parts > 1) {
         // the candidate arrays last used on this stream, else the set whose turn it is (after its last user)

@@ -428,6 +428,50 @@ def test_selection_on_the_gathers_stream(Hq, Hkv, dtype, bits, g, form, mixed):
         c.close()
 
 
+def test_repeated_selection_and_slot_refill_across_streams():
+    """Call sequences a stepping loop does not produce, which the library still has to order: the same keys
+    selected twice, on two side streams, into both slots; a slot refilled from another stream than its last
+    gather; then the layer's next scoring pass, which overwrites those keys.  Every index list must equal the one
+    a context with everything on the caller's stream produces, and attention on either slot the same output."""
+    from tests.harness import to_dev
+    S, k, dtype, seed, Hq = 5000, 200, synth.FP16, 3300, 2
+    kb, vb = synth.make_kv(seed, 1, Hq, S, 128, dtype)
+    main, sa, sb = torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    res = {}
+    for mode in (0, 2):
+        sc = binding.SpeCache(1, 1, Hq, Hq, 2, 32, 5120, k, dtype, async_select=mode)
+        try:
+            sc.quantize_append(0, to_dev(kb, dtype), to_dev(vb, dtype), S)
+            idx = [torch.full((1, Hq, k), -7, dtype=torch.int32, device="cuda") for _ in range(6)]
+            outs = [torch.empty((1, Hq, 2, 128), dtype=torch.float32, device="cuda") for _ in range(4)]
+            got = []
+            for t in range(3):
+                q = to_dev(synth.make_queries(seed, 1, Hq, 128, dtype, n_rows=2, sub=t), dtype)
+                a, b = idx[2 * t], idx[2 * t + 1]
+                if mode == 2:
+                    sc.score(0, q, 2, main)
+                    sc.select_gather(0, a, 0, sa)
+                    sc.select_gather(0, b, 1, sb)       # same keys again, other stream, other slot
+                    sc.gather(0, a, 1, sa)               # slot 1 refilled from the other stream
+                else:
+                    sc.score_topk(0, q, 2, a, main)
+                    sc.score_topk(0, q, 2, b, main)
+                    sc.gather(0, a, 0, main)
+                    sc.gather(0, a, 1, main)
+                sc.attend(0, q, 2, None, None, 0, outs[0], main)
+                sc.attend(0, q, 2, None, None, 1, outs[1], main)
+                torch.cuda.synchronize()
+                got.append((a.cpu().numpy().copy(), b.cpu().numpy().copy(), outs[0].cpu().numpy().copy(), outs[1].cpu().numpy().copy()))
+            res[mode] = got
+        finally:
+            torch.cuda.synchronize()
+            sc.close()
+    for (a0, b0, o00, o01), (a2, b2, o20, o21) in zip(res[0], res[2]):
+        assert np.array_equal(a0, b0) and np.array_equal(a2, b2) and np.array_equal(a0, a2)
+        assert np.array_equal(o00, o20) and np.array_equal(o01, o21) and np.array_equal(o00, o01)
+        assert (a0 >= 0).sum() == Hq * k
+
+
 def test_two_launch_selection_on_two_gather_streams():
     """async_select = 2 with rows long enough for the two-launch ArgTopK (> 65536 keys): the selections of
     consecutive layers run on different side streams and may overlap, each with candidate arrays of its own.
