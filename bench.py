@@ -354,7 +354,9 @@ def main():
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend on the "
                                    "main stream, gather of the next step's pairs on side streams",
                    "side_streams": len(side_list) if not args.serial_gather else 0,
-                   "async_select": int(async_select)},
+                   "async_select": int(async_select),
+                   "calls_per_layer": ("quantize_append, score, select_gather, attend" if async_select == 2 and args.variant == "speculative"
+                                       else "quantize_append, score_topk, gather, attend")},
         "score_topk_attend_us": breakdown["score_topk_attend"],
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),
         "kernel_us_no_gather": per_kernel_ng,
