@@ -115,6 +115,9 @@ def main():
                          "(the specache_score / specache_select_gather pair of calls); auto = main for one layer and for the "
                          "non-speculative variant, else gather where a fetched pair stands for 96 or more scored keys "
                          "(the step is bound by compute and by the issuing thread) and own below that (bound by the link)")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="with ArgTopK on the gather's stream: issue quantize_append and score as two calls instead of "
+                         "specache_append_score (whose scoring launch carries the copy of the new pair)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -248,11 +251,15 @@ def main():
         slot = (t % 2) if (t > 0 and not args.no_gather) else -1
         for L in range(layers):
             q = q_p[t % nq_pool][L]
-            sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
             if async_select == 2:
-                sc.score(L, q, 2, main_h)
+                if args.separate_append:
+                    sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
+                    sc.score(L, q, 2, main_h)
+                else:
+                    sc.append_score(L, k_p[t], v_p[t], q, 2, main_h)   # the scoring launch carries the append
                 sc.select_gather(L, idx_p[L][t % 2], (t + 1) % 2 if do_gather else -1, side_h[L % len(side_h)])
             else:
+                sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
                 sc.score_topk(L, q, 2, idx_p[L][t % 2], main_h)
                 if do_gather:
                     sc.gather(L, idx_p[L][t % 2], (t + 1) % 2, side_h[L % len(side_h)])
@@ -355,7 +362,8 @@ def main():
                                    "main stream, gather of the next step's pairs on side streams",
                    "side_streams": len(side_list) if not args.serial_gather else 0,
                    "async_select": int(async_select),
-                   "calls_per_layer": ("quantize_append, score, select_gather, attend" if async_select == 2 and args.variant == "speculative"
+                   "calls_per_layer": (("quantize_append, score, select_gather, attend" if args.separate_append else
+                                        "append_score, select_gather, attend") if async_select == 2 and args.variant == "speculative"
                                        else "quantize_append, score_topk, gather, attend")},
         "score_topk_attend_us": breakdown["score_topk_attend"],
         "compute_us_layer": (round(compute_ms * 1e3 / layers, 3) if compute_ms else None),

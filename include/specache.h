@@ -203,6 +203,19 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
  * Errors: EINVAL, ESTATE (wrong mode; select_gather without a specache_score before it).
  */
 int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream);
+
+/*
+ * specache_quantize_append of ONE token followed by specache_score, as one call (same context
+ * mode as specache_score).  k_new, v_new: device, 16-bit, [B, Hkv, 1, 128], as in
+ * specache_quantize_append; q, n_rows, stream as in specache_score.  When the token does not
+ * complete a group that leaves the residual, the scoring launch itself carries the Offload
+ * of the new pair (Appendix A "Decoding") to the CPU copy and to the residual, which saves
+ * a kernel launch per layer-step; otherwise the two steps run one after the other.  Results
+ * are those of the two calls.
+ * Errors: those of the two calls.
+ */
+int specache_append_score(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                          int32_t n_rows, void* stream);
 int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream);
 
 /*

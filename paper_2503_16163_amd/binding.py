@@ -17,7 +17,7 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
-           "specache_score", "specache_select_gather",
+           "specache_score", "specache_select_gather", "specache_append_score",
            "specache_attend", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
            "specache_timing"]
 
@@ -57,6 +57,7 @@ def lib():
         L.specache_gather.argtypes = [vp, i32, vp, i32, vp]
         L.specache_score.argtypes = [vp, i32, vp, i32, vp]
         L.specache_select_gather.argtypes = [vp, i32, vp, i32, vp]
+        L.specache_append_score.argtypes = [vp, i32, vp, vp, vp, i32, vp]
         L.specache_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
         L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
         L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
@@ -133,6 +134,9 @@ class SpeCache:
 
     def score(self, layer, q, n_rows, stream=None):
         self._check(lib().specache_score(self._ctx, layer, _ptr(q), n_rows, _stream(stream)))
+
+    def append_score(self, layer, k_new, v_new, q, n_rows, stream=None):
+        self._check(lib().specache_append_score(self._ctx, layer, _ptr(k_new), _ptr(v_new), _ptr(q), n_rows, _stream(stream)))
 
     def select_gather(self, layer, topk_idx_out, slot, side_stream=None):
         self._check(lib().specache_select_gather(self._ctx, layer, _ptr(topk_idx_out), slot, _stream(side_stream)))

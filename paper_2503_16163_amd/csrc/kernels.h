@@ -22,6 +22,11 @@ struct LayerView {
     uint16_t* ring;    // residual  [rows][R][256] 16-bit
     uint16_t* host;    // pinned C  [rows][max_seq][256] 16-bit (device-visible address)
     size_t kc_stride, km_stride, vc_stride, vm_stride;
+    // Set for one scoring launch only (specache_append_score): the new token's (K, V) pair, which one
+    // extra workgroup per row copies to the host store and the residual ring as token tail_N0.
+    const uint16_t* tail_k = nullptr;   // [rows][128] 16-bit, null: nothing to append
+    const uint16_t* tail_v = nullptr;
+    int tail_N0 = 0;
 };
 
 // quantize_append: flush `n_flush` groups starting at token Nq0, whose sources are

@@ -117,6 +117,22 @@ __host__ __device__ __forceinline__ size_t v_byte_offset(int t, int L) {
     return (size_t)blk * code_block_bytes(BITS) + ((size_t)half * (16 * BITS) + L) * 16 + tt;
 }
 
+// Offload of one new token by the scoring launch's extra workgroup of a row (Appendix A "Decoding":
+// the new pair goes to the CPU copy; it also joins the 16-bit residual): 32 lanes x 16 B move the
+// 512-byte (K,V) pair.  True when this workgroup was that extra one.
+template <typename View>
+__device__ __forceinline__ bool append_tail_block(const View& L, int row) {
+    if (L.tail_k == nullptr || blockIdx.x != gridDim.x - 1) return false;
+    const int part = threadIdx.x;
+    if (part < 32) {
+        const uint4 v = reinterpret_cast<const uint4*>(part < 16 ? L.tail_k : L.tail_v)[(size_t)row * 16 + (part & 15)];
+        const int t = L.tail_N0;
+        reinterpret_cast<uint4*>(L.host)[((size_t)row * L.max_seq + t) * 32 + part] = v;
+        reinterpret_cast<uint4*>(L.ring)[((size_t)row * L.R + (t % L.R)) * 32 + part] = v;
+    }
+    return true;
+}
+
 // order-preserving map float -> uint32 (larger float <=> larger key); -0 joins +0
 __device__ __forceinline__ uint32_t float_to_key(float f) {
     const uint32_t u = __float_as_uint(f + 0.0f);

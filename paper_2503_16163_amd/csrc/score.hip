@@ -72,6 +72,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, k = lane & 3;
     const int row = blockIdx.y, tile = blockIdx.x;
+    if (append_tail_block(L, row)) return;   // the extra workgroup of a fused append
     const int n_sub = Nq / kBlockTokens;                       // quantised 32-token sub-groups
     const int sub = tile * 16 + (lane >> 2);
     const bool active = sub < n_sub;
@@ -256,7 +257,7 @@ __global__ __launch_bounds__(64 * kScoreWaves) void score_kernel(LayerView L, co
 template <int BITS, int G, int NROWS>
 hipError_t launch3(const LayerView& L, const void* q, int Nq, float sm_scale, float* logits, size_t logit_stride,
                    uint32_t* keys, size_t key_stride, hipStream_t stream) {
-    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kScoreWaves);
+    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens + (L.tail_k ? 1 : 0), L.rows), block(64 * kScoreWaves);
     if (L.bf16)
         SPC_LAUNCH((score_kernel<BITS, G, NROWS, true>), grid, block, stream, L, (const uint16_t*)q, Nq,
                            sm_scale, logits, logit_stride, keys, key_stride);

@@ -103,6 +103,7 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(8, 
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row = blockIdx.y, tile = blockIdx.x;
+    if (append_tail_block(L, row)) return;   // the extra workgroup of a fused append
     const int n_sub = Nq / kBlockTokens;                       // quantised 32-token sub-groups
     const int sub0 = tile * 16 + 4 * wave;                     // this wave's first sub-group
     if (sub0 >= n_sub) return;                                 // the waves never meet at a barrier
@@ -273,7 +274,7 @@ hipError_t launch_score_i8(const LayerView& L, const void* q, int Nq, float sm_s
                            size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream) {
     if (L.G != 1 || (L.bits != 1 && L.bits != 2) || (L.group != 32 && L.group != 64 && L.group != 128) || Nq % L.group != 0)
         return hipErrorInvalidValue;
-    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kWaves);
+    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens + (L.tail_k ? 1 : 0), L.rows), block(64 * kWaves);
 #define SPC_I8(B_, F_)                                                                                         \
     SPC_LAUNCH((score_i8_kernel<B_, F_>), grid, block, stream, L, (const uint16_t*)q, Nq, sm_scale, logits, \
                logit_stride, keys, key_stride)

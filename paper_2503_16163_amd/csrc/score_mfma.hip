@@ -68,6 +68,7 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(LayerView L, co
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ic = lane & 15, kq = lane >> 4;
     const int row = blockIdx.y, tile = blockIdx.x;
+    if (append_tail_block(L, row)) return;   // the extra workgroup of a fused append
     const int n_sub = Nq / kBlockTokens;
 
     // This lane's multipliers-to-be.  Column (r, hi | lo) needs sm_scale * q[r][32 kc + 8 kq + e],
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(64 * kWaves) void score_mfma_kernel(LayerView L, co
 template <int BITS, int G, int NROWS>
 hipError_t launch_case(const LayerView& L, const void* q, int Nq, float sm_scale, float* logits, size_t logit_stride,
                        uint32_t* keys, size_t key_stride, hipStream_t stream) {
-    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens, L.rows), block(64 * kWaves);
+    const dim3 grid((Nq + kTileTokens - 1) / kTileTokens + (L.tail_k ? 1 : 0), L.rows), block(64 * kWaves);
     if (L.bf16)
         SPC_LAUNCH((score_mfma_kernel<BITS, G, NROWS, true>), grid, block, stream, L, (const uint16_t*)q, Nq,
                            sm_scale, logits, logit_stride, keys, key_stride);

@@ -206,10 +206,11 @@ void free_all(specache_ctx* ctx) {
 
 // The scoring pass of one layer on stream st: low-bit logits of every query row, selection keys of
 // the last row, and the optional rewrites of those keys (mixed-cache selection, log-probability form).
-int score_phase(specache_ctx* ctx, Layer& L, const void* q, int n_rows, uint32_t* keys, hipStream_t st) {
+int score_phase(specache_ctx* ctx, Layer& L, const void* q, int n_rows, uint32_t* keys, hipStream_t st,
+                const LayerView* fused_view = nullptr) {
     if (L.Nq > 0) {
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
-        SPC_HIP(ctx, launch_score(L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, keys,
+        SPC_HIP(ctx, launch_score(fused_view ? *fused_view : L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, keys,
                                   ctx->logit_stride, st));
         // selection on the mixed cache: the positions staged by the layer's last gather are scored with
         // their 16-bit keys (that slot is the one the coming attend reads; the next gather into it
@@ -496,7 +497,9 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     return SPECACHE_OK;
 }
 
-int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream) {
+// specache_score, optionally with the copy of one new token carried by the scoring launch
+static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream, const void* k_new,
+                      const void* v_new) {
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!ctx->select_on_gather) return fail(ctx, SPECACHE_ESTATE, "specache_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
     if (!q) return fail(ctx, SPECACHE_EINVAL, "null q");
@@ -517,7 +520,17 @@ int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_ro
         if (L.selected_stream != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.selected, 0));
         L.selected_pending = false;
     }
-    if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) return rc;
+    if (k_new) {
+        // the scoring launch appends token N: one more workgroup per row copies the pair
+        LayerView fused = L.view;
+        fused.tail_k = (const uint16_t*)k_new;
+        fused.tail_v = (const uint16_t*)v_new;
+        fused.tail_N0 = L.N;
+        L.N += 1;
+        if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused)) return rc;
+    } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) {
+        return rc;
+    }
     // "scored": what the selection waits for, and what orders a gather after the attends enqueued so far
     SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;
@@ -531,6 +544,29 @@ int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_ro
     ctx->scored_N = L.N;
     ctx->scored_Nq = L.Nq;
     return SPECACHE_OK;
+}
+
+int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream) {
+    return score_impl(ctx, layer, q, n_rows, stream, nullptr, nullptr);
+}
+
+int specache_append_score(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                          int32_t n_rows, void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!ctx->select_on_gather)
+        return fail(ctx, SPECACHE_ESTATE, "specache_append_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    if (!k_new || !v_new) return fail(ctx, SPECACHE_EINVAL, "null k_new or v_new");
+    Layer& L = ctx->layers[layer];
+    if ((long)L.N + 1 > ctx->cfg.max_seq) return fail(ctx, SPECACHE_ECAPACITY, "append exceeds max_seq");
+    int32_t n_flush = 0;
+    if (specache_plan_append(ctx->cfg.residual, ctx->cfg.group, L.N, L.Nq, 1, &n_flush) != SPECACHE_OK)
+        return fail(ctx, SPECACHE_ESTATE, "inconsistent token counts");
+    // a group leaves the residual with this token, or nothing is quantised yet (no scoring launch): two steps
+    if (n_flush > 0 || L.Nq == 0) {
+        if (int rc = specache_quantize_append(ctx, layer, k_new, v_new, 1, stream)) return rc;
+        return score_impl(ctx, layer, q, n_rows, stream, nullptr, nullptr);
+    }
+    return score_impl(ctx, layer, q, n_rows, stream, k_new, v_new);
 }
 
 int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream) {

@@ -63,7 +63,8 @@ class Case:
     """One configuration run on both sides.  `sample` lists the (b, hkv) pairs the oracle mirrors."""
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
-                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0, async_select=0):
+                 max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0, async_select=0,
+                 fused_append=False):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
@@ -71,6 +72,8 @@ class Case:
         cap = max_seq or ((S + 64 + 63) // 64) * 64
         self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
         self.async_select = async_select
+        self.fused_append = bool(fused_append) and async_select == 2   # specache_append_score in decode_step
+        self.pending = None
         self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
                                    select_form=select_form, select_cache=select_cache, async_select=async_select)
@@ -105,14 +108,24 @@ class Case:
 
     def append_token(self, t):
         kb, vb = synth.make_step_kv(self.seed, t, self.B, self.Hkv, self.D, self.dtype)
-        self.sc.quantize_append(0, to_dev(kb, self.dtype), to_dev(vb, self.dtype), 1)
+        self._flush_pending()
+        if self.fused_append:
+            self.pending = (to_dev(kb, self.dtype), to_dev(vb, self.dtype))   # appended by the next decode_step
+        else:
+            self.sc.quantize_append(0, to_dev(kb, self.dtype), to_dev(vb, self.dtype), 1)
         for (b, h) in self.sample:
             self.oc[(b, h)].append(kb[b, h], vb[b, h])
         self.step_k.append(kb)
         self.step_v.append(vb)
 
+    def _flush_pending(self):
+        if self.pending is not None:
+            self.sc.quantize_append(0, self.pending[0], self.pending[1], 1)
+            self.pending = None
+
     # ---- checks -------------------------------------------------------------
     def check_quantized(self):
+        self._flush_pending()
         e = self.sc.export_quantized(0)
         n, nq = self.sc.counts(0)
         for (b, h) in self.sample:
@@ -128,6 +141,7 @@ class Case:
         return n, nq
 
     def check_offload(self, first=0, count=None):
+        self._flush_pending()
         n, _ = self.sc.counts(0)
         count = n - first if count is None else count
         rows = self.sc.export_rows(0, first, count)
@@ -152,7 +166,11 @@ class Case:
         idx = self.idx[t % 2]
         main = torch.cuda.current_stream()
         if self.async_select == 2:   # ArgTopK on the gather's stream: the other pair of calls
-            self.sc.score(0, q, nr, main)
+            if self.pending is not None:
+                self.sc.append_score(0, self.pending[0], self.pending[1], q, nr, main)
+                self.pending = None
+            else:
+                self.sc.score(0, q, nr, main)
             self.sc.select_gather(0, idx, (t + 1) % 2 if do_gather else -1, self.side)
         else:
             self.sc.score_topk(0, q, nr, idx, main)
@@ -199,6 +217,7 @@ class Case:
         q = to_dev(q_bits, self.dtype)
         idx = self.idx[t % 2]
         main = torch.cuda.current_stream()
+        self._flush_pending()
         self.sc.score_topk(0, q, 1, idx, main)
         self.sc.gather(0, idx, 0, main)
         out = torch.empty((self.B, self.Hq, 1, self.D), dtype=torch.float32, device="cuda")

@@ -428,6 +428,30 @@ def test_selection_on_the_gathers_stream(Hq, Hkv, dtype, bits, g, form, mixed):
         c.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,dtype,bits,g,R", [(2, 2, synth.FP16, 2, 32, 64),      # integer matrix-core scoring kernel
+                                                    (8, 2, synth.BF16, 1, 32, 64),      # 8 rows per KV head: matrix-core kernel
+                                                    (4, 2, synth.FP16, 2, 64, 128),     # vector-ALU kernel
+                                                    (3, 3, synth.BF16, 2, 128, 128)])
+def test_append_carried_by_the_scoring_launch(Hq, Hkv, dtype, bits, g, R):
+    """specache_append_score: the new token's pair reaches the host copy and the residual from inside the scoring
+    launch (one extra workgroup per row) on steps that flush nothing, and through the two separate steps on the
+    others.  80 decode steps cross several flushes; every step's selection and attention output (the residual
+    holds the newest token) are checked against the oracle, and at the end the quantised prefix and every
+    offloaded row."""
+    from tests.harness import Case
+    c = Case(1, Hq, Hkv, 1000, dtype, bits, g, 40, R=R, seed=3400 + Hq + g, async_select=2, fused_append=True)
+    try:
+        c.load()
+        for t in range(80):
+            c.append_token(t)
+            c.decode_step(check_logits=(t % 16 == 0))
+        c.check_quantized()
+        c.check_offload(first=c.S, count=80)
+        assert c.sc.counts(0)[0] == 1080
+    finally:
+        c.close()
+
+
 def test_repeated_selection_and_slot_refill_across_streams():
     """Call sequences a stepping loop does not produce, which the library still has to order: the same keys
     selected twice, on two side streams, into both slots; a slot refilled from another stream than its last
@@ -573,6 +597,7 @@ def test_error_paths():
             (lambda: sc.attend(0, q, 2, None, None, -1, out), binding.ESTATE),   # nothing scored
             (lambda: sc.score(0, q, 2), binding.ESTATE),                         # context not created for that pair of calls
             (lambda: sc.select_gather(0, idx, 0), binding.ESTATE),
+            (lambda: sc.append_score(0, k, k, q, 2), binding.ESTATE),
         ]:
             with pytest.raises(binding.SpeCacheError) as ei:
                 fn()
