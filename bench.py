@@ -115,9 +115,10 @@ def main():
                          "(the specache_score / specache_select_gather pair of calls); auto = main for one layer and for the "
                          "non-speculative variant, else gather where a fetched pair stands for 96 or more scored keys "
                          "(the step is bound by compute and by the issuing thread) and own below that (bound by the link)")
-    ap.add_argument("--separate-append", action="store_true",
-                    help="with ArgTopK on the gather's stream: issue quantize_append and score as two calls instead of "
-                         "specache_append_score (whose scoring launch carries the copy of the new pair)")
+    ap.add_argument("--fused-append", action="store_true",
+                    help="with ArgTopK on the gather's stream: specache_append_score (the scoring launch carries the copy of "
+                         "the new pair) instead of quantize_append and score as two calls.  1 to 3 us per layer faster; off "
+                         "by default so that every step of the path keeps a kernel and a timing of its own")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -252,7 +253,7 @@ def main():
         for L in range(layers):
             q = q_p[t % nq_pool][L]
             if async_select == 2:
-                if args.separate_append:
+                if not args.fused_append:
                     sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
                     sc.score(L, q, 2, main_h)
                 else:
@@ -362,7 +363,7 @@ def main():
                                    "main stream, gather of the next step's pairs on side streams",
                    "side_streams": len(side_list) if not args.serial_gather else 0,
                    "async_select": int(async_select),
-                   "calls_per_layer": (("quantize_append, score, select_gather, attend" if args.separate_append else
+                   "calls_per_layer": (("quantize_append, score, select_gather, attend" if not args.fused_append else
                                         "append_score, select_gather, attend") if async_select == 2 and args.variant == "speculative"
                                        else "quantize_append, score_topk, gather, attend")},
         "score_topk_attend_us": breakdown["score_topk_attend"],
