@@ -153,10 +153,11 @@ def main():
     # gather's stream, which needs the fewest ordering calls between streams.  With little of it the step is
     # bound by the host link: ArgTopK on the library's own stream lets every gather start the moment its
     # selection is done.  One layer, or the non-speculative variant: everything on the main stream.
-    keys_per_pair = G * S / k
+    from paper_2503_16163_amd import arrangement
     side_gathers = args.variant == "speculative" and not args.serial_gather and not args.no_gather
+    auto_select, _ = arrangement.pick(G, S, k, layers, args.variant == "speculative", side_gathers)
     if args.select_stream == "auto":
-        async_select = 0 if (layers == 1 or args.variant != "speculative") else (2 if side_gathers and keys_per_pair >= 96 else 1)
+        async_select = auto_select
     else:
         async_select = {"main": 0, "own": 1, "gather": 2 if side_gathers else 1}[args.select_stream]
     sc = None
@@ -171,12 +172,7 @@ def main():
                 raise
             layers = max(1, layers // 2)   # the pinned host store did not fit: fewer layers
     main_s = torch.cuda.current_stream()
-    if args.side_streams > 0:
-        n_side = args.side_streams
-    elif async_select == 2:
-        n_side = 3 if keys_per_pair < 192 else 2   # a third stream selects while two gathers share the link
-    else:
-        n_side = 1 if keys_per_pair >= 384 else 2
+    n_side = args.side_streams if args.side_streams > 0 else arrangement.side_streams(async_select, G, S, k)
     side_list = [main_s] if args.serial_gather else [torch.cuda.Stream() for _ in range(n_side)]
 
     # ---- load the prompt: the same synthetic K/V tensor serves every layer ----------
@@ -347,9 +343,9 @@ def main():
             roofline["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(score_name)
         except Exception:
             roofline["traffic"] = None
-    attend_us = per_kernel_us["attend"]
+    attend_us = per_kernel_us["attend"] + (per_kernel_us["attend_combine"] or 0.0)
     breakdown = {n: (round(v, 3) if v is not None else None) for n, v in per_kernel_us.items()}
-    breakdown["score_topk_attend"] = round(sum(per_kernel_us[n] for n in ("score", "topk", "attend")), 3)
+    breakdown["score_topk_attend"] = round(sum(per_kernel_us[n] or 0.0 for n in ("score", "topk", "attend", "attend_combine")), 3)
     result = {
         "metric": "us per layer decode step (score+top-k+attend) + achieved HBM GB/s, 7B shape 32k ctx"
                   if args.workload == "M0" else "us per layer decode step (score+top-k+attend) + achieved HBM GB/s",

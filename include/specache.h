@@ -25,6 +25,10 @@
  *   - Calls on one context must come from one host thread at a time.
  *   - A context keeps one score scratch: specache_attend(layer) must follow the
  *     specache_score_topk of the same layer with no other layer scored between.
+ *   - The append, the scoring call and the attend of a layer are ordered by stream
+ *     order only (the residual ring and the score scratch carry no events of their
+ *     own): pass all three the same stream.  Only the staging slots, the index
+ *     lists and the selection keys are ordered across streams by the library.
  */
 #ifndef SPECACHE_H
 #define SPECACHE_H
@@ -57,7 +61,8 @@ enum { SPECACHE_SELECT_LOWBIT = 0, SPECACHE_SELECT_MIXED = 1 };
 typedef struct specache_config {
     int32_t n_layers;   /* >= 1                                                        */
     int32_t batch;      /* B >= 1                                                      */
-    int32_t n_q_heads;  /* Hq, a multiple of n_kv_heads; Hq / Hkv in {1, 2, 4, 8}      */
+    int32_t n_q_heads;  /* Hq, a multiple of n_kv_heads; Hq / Hkv in {1, 2, 4, 8} (with the
+                           two query rows of a decode step: up to 16 rows per KV head) */
     int32_t n_kv_heads; /* Hkv >= 1                                                    */
     int32_t head_dim;   /* must be 128                                                 */
     int32_t bits;       /* 1 (Eq. 3) or 2 (Eq. 2)                                      */
@@ -148,8 +153,8 @@ int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new
 /*
  * Low-bit scoring and ArgTopK (Appendix A "Decoding": A = Softmax(Q K^T) on the
  * low-bit keys, K_{t+1} = ArgTopK(A_{1,:}); "Pre-decoding" with n_rows = 1).
- * q: device, 16-bit, [B, Hq, n_rows, 128], n_rows in {1, 2}; row 0 is the output
- * token's query, row 1 the speculative token's.  For every quantised position
+ * q: device, 16-bit, [B, Hq, n_rows, 128], 16-byte aligned, n_rows in {1, 2}; row 0 is
+ * the output token's query, row 1 the speculative token's.  For every quantised position
  * i < Nq and every query head the logit sm_scale * q . K'_i is computed from the
  * packed keys (read once for all rows and heads of a KV head) and kept in the
  * context for the following specache_attend.  The selection score of position i
@@ -158,8 +163,8 @@ int specache_quantize_append(specache_ctx* ctx, int32_t layer, const void* k_new
  * complete); receives the min(k, Nq)
  * positions with the largest selection score (ties to the lower index) in
  * ascending index order, the rest -1.
- * Errors: EINVAL, ESTATE (no call order requirement fails here; Nq = 0 is
- * allowed and yields all -1).
+ * Errors: EINVAL (also a q that is not 16-byte aligned), ESTATE (no call order
+ * requirement fails here; Nq = 0 is allowed and yields all -1).
  */
 int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows,
                         int32_t* topk_idx_out, void* stream);
@@ -203,6 +208,7 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
  * Errors: EINVAL, ESTATE (wrong mode; select_gather without a specache_score before it).
  */
 int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream);
+int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream);
 
 /*
  * specache_quantize_append of ONE token followed by specache_score, as one call (same context
@@ -216,7 +222,6 @@ int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_ro
  */
 int specache_append_score(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
                           int32_t n_rows, void* stream);
-int specache_select_gather(specache_ctx* ctx, int32_t layer, int32_t* topk_idx_out, int32_t slot, void* side_stream);
 
 /*
  * Mixed attention, Eq. 1: O = Attn([T_t, T'_{t+1}], C' u C_K).
@@ -254,13 +259,25 @@ int specache_export_rows(specache_ctx* ctx, int32_t layer, int32_t first, int32_
 int specache_debug_logits(specache_ctx* ctx, float* out);
 
 /*
+ * Test hook for the two-stream staging protocol: enqueues on `stream` a fill of staging slot
+ * `slot` (0 or 1) of the layer with 0xFFFF words, a NaN in binary16 and bfloat16 alike, so that
+ * an attend that reads the slot before the next gather has rewritten it returns NaNs.  The
+ * slot's index list is left as it is.  The caller orders the fill (put it on the stream of the
+ * attend that read the slot last, behind that attend).
+ * Errors: EINVAL.
+ */
+int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream);
+
+/*
  * Measurement hook.  While enabled, every hot call brackets each of its kernel
  * phases with a pair of HIP events on the stream the phase is launched on.
  * specache_timing synchronises the device, adds up the elapsed time of all
  * pairs recorded since the previous call into total_us[SPECACHE_K_COUNT] (host,
  * microseconds) and launches[SPECACHE_K_COUNT] (host), forgets them, and then
  * switches recording on (enable != 0) or off.  Either output may be NULL.
- * SPECACHE_K_ATTEND covers the partial and the combine kernel together.
+ * The scoring, ArgTopK and attention kernels are timed by events that their own dispatch
+ * packets carry (start and stop of the kernel as a profiler sees them); the other phases by
+ * event records around the launch.
  */
 enum {
     SPECACHE_K_FLUSH = 0,       /* quantise + pack of full groups            */
@@ -268,10 +285,25 @@ enum {
     SPECACHE_K_SCORE = 2,       /* fused dequantise + q.K^T                  */
     SPECACHE_K_TOPK = 3,        /* radix select + ordered compaction         */
     SPECACHE_K_GATHER = 4,      /* host-link gather (side stream)            */
-    SPECACHE_K_ATTEND = 5,      /* mixed attention: partial + combine        */
-    SPECACHE_K_COUNT = 6
+    SPECACHE_K_ATTEND = 5,      /* mixed attention: partial pass over chunks */
+    SPECACHE_K_ATTEND_COMBINE = 6, /* mixed attention: merge of the chunks    */
+    SPECACHE_K_COUNT = 7
 };
 int specache_timing(specache_ctx* ctx, int32_t enable, double* total_us, int64_t* launches);
+
+/*
+ * Roofline denominators, measured on the current HIP device (no context; each call allocates
+ * its buffers, synchronises, and frees them; not part of the decode path).
+ * specache_measure_hbm_read: median rate, in GB/s (1e9 bytes/s), of `reps` launches of a plain
+ *   kernel that reads `bytes` of device memory once with 16-byte loads (after one untimed launch).
+ * specache_measure_link: the same for the host link, over `bytes` of pinned host memory:
+ *   *memcpy_gbs for hipMemcpyAsync to device memory, *kernel_gbs for a kernel that reads the
+ *   pinned buffer directly (contiguously; the gather of Section 3.3's prefetch reads 512-byte
+ *   rows the same way).  Either output may be NULL.
+ * bytes >= 1 MiB, 1 <= reps <= 1000.  Errors: EINVAL, ENOMEM, EHIP.
+ */
+int specache_measure_hbm_read(int64_t bytes, int32_t reps, double* gbs);
+int specache_measure_link(int64_t bytes, int32_t reps, double* memcpy_gbs, double* kernel_gbs);
 
 #ifdef __cplusplus
 }

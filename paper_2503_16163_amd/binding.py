@@ -18,8 +18,8 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
            "specache_score", "specache_select_gather", "specache_append_score",
-           "specache_attend", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
-           "specache_timing"]
+           "specache_attend", "specache_debug_poison_slot", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
+           "specache_timing", "specache_measure_hbm_read", "specache_measure_link"]
 
 
 class Config(C.Structure):
@@ -39,11 +39,16 @@ _lib = None
 
 
 def lib():
-    """Load libspecache.so (building it first only if it was never built)."""
+    """Load libspecache.so.  It is built first if it was never built; a library older than its
+    sources is an error (build again: python -m paper_2503_16163_amd.build), so that tests and
+    timings never run on a stale build unnoticed."""
     global _lib
     if _lib is None:
         if not os.path.exists(_build.LIB):
             _build.build()
+        elif not _build.is_built():
+            raise RuntimeError("libspecache.so is older than its sources under csrc/ or include/specache.h: "
+                               "run `python -m paper_2503_16163_amd.build` (or __graft_entry__.build())")
         L = C.CDLL(_build.LIB)
         vp, i32 = C.c_void_p, C.c_int32
         L.specache_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
@@ -59,10 +64,13 @@ def lib():
         L.specache_select_gather.argtypes = [vp, i32, vp, i32, vp]
         L.specache_append_score.argtypes = [vp, i32, vp, vp, vp, i32, vp]
         L.specache_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
+        L.specache_debug_poison_slot.argtypes = [vp, i32, i32, vp]
         L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
         L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
         L.specache_debug_logits.argtypes = [vp, vp]
         L.specache_timing.argtypes = [vp, i32, vp, vp]
+        L.specache_measure_hbm_read.argtypes = [C.c_int64, i32, C.POINTER(C.c_double)]
+        L.specache_measure_link.argtypes = [C.c_int64, i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         for name in EXPORTS:
             if name != "specache_last_error":
                 getattr(L, name).restype = C.c_int
@@ -95,6 +103,24 @@ def plan_append(residual, group, n_tokens, n_quantized, n_new):
     if rc != OK:
         raise SpeCacheError(rc, "plan_append: inconsistent arguments")
     return out.value
+
+
+def measure_hbm_read(nbytes=1 << 30, reps=10):
+    """GB/s of a plain 128-bit streaming read of `nbytes` of device memory (median of `reps` launches)."""
+    out = C.c_double()
+    rc = lib().specache_measure_hbm_read(nbytes, reps, C.byref(out))
+    if rc != OK:
+        raise SpeCacheError(rc, "measure_hbm_read failed")
+    return out.value
+
+
+def measure_link(nbytes=256 << 20, reps=5):
+    """(memcpy GB/s, zero-copy read kernel GB/s) of the host link over `nbytes` of pinned host memory."""
+    a, b = C.c_double(), C.c_double()
+    rc = lib().specache_measure_link(nbytes, reps, C.byref(a), C.byref(b))
+    if rc != OK:
+        raise SpeCacheError(rc, "measure_link failed")
+    return a.value, b.value
 
 
 class SpeCache:
@@ -148,7 +174,10 @@ class SpeCache:
         self._check(lib().specache_attend(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
                                           _ptr(out), _stream(stream)))
 
-    KERNELS = ("flush", "append_copy", "score", "topk", "gather", "attend")
+    def debug_poison_slot(self, layer, slot, stream=None):
+        self._check(lib().specache_debug_poison_slot(self._ctx, layer, slot, _stream(stream)))
+
+    KERNELS = ("flush", "append_copy", "score", "topk", "gather", "attend", "attend_combine")
 
     def timing(self, enable):
         """Collect and reset per-kernel event timings; returns {kernel: (total_us, launches)}."""

@@ -1,4 +1,5 @@
 """Compile the HIP sources under csrc/ into paper_2503_16163_amd/libspecache.so for gfx950."""
+import hashlib
 import os
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
@@ -7,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecache.so")
-SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "select.hip", "topk.hip", "gather.hip", "attend.hip"]
+STAMP = os.path.join(HERE, "libspecache.srchash")   # hash of the sources the library was built from
+SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "select.hip", "topk.hip", "gather.hip", "attend.hip", "measure.hip"]
 # -ffp-contract=off: the quantiser's binary32 operation order is part of its definition and
 # fused multiply-adds are written out where they are wanted.  Packed FP32 code generation is
 # switched off for the device pass.
@@ -38,15 +40,29 @@ def build(verbose=False):
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
+    with open(STAMP, "w") as f:
+        f.write(source_hash())
     return LIB
 
 
+def source_hash():
+    """sha256 over the HIP sources, their headers and the C ABI header (names and contents)."""
+    h = hashlib.sha256()
+    deps = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC)) + [os.path.join(HERE, "..", "include", "specache.h")]
+    for d in deps:
+        h.update(os.path.basename(d).encode())
+        with open(d, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_built():
-    if not os.path.exists(LIB):
+    """True when libspecache.so exists and was built from the sources as they are now (by content, so that
+    a copy of the tree to another machine does not look stale)."""
+    if not (os.path.exists(LIB) and os.path.exists(STAMP)):
         return False
-    t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(HERE, "..", "include", "specache.h")]
-    return all(os.path.getmtime(d) <= t for d in deps)
+    with open(STAMP) as f:
+        return f.read().strip() == source_hash()
 
 
 if __name__ == "__main__":

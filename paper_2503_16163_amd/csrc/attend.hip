@@ -833,30 +833,33 @@ __global__ __launch_bounds__(kCombineThreads) void attend_combine_kernel(const f
 }
 
 template <int BITS, int GROUP, int G, int NROWS>
-hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* out, hipStream_t stream) {
+hipError_t launch3(const LayerView& L, const AttendArgs& A, int n_extra, float* out, int phases, hipStream_t stream) {
     constexpr int NR = G * NROWS;
     if (A.n_main + n_extra > kCombineMaxChunks) return hipErrorInvalidValue;
-    const dim3 grid((A.n_main + n_extra) * L.rows), block(kThreads);
-    if (L.bf16)
-        hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, true>), grid, block, 0, stream, L, A);
-    else
-        hipLaunchKernelGGL((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, 0, stream, L, A);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(attend_combine_kernel, dim3(L.rows * NR), dim3(kCombineThreads), 0, stream, A.part_o, A.part_ml,
-                       A.max_chunks, A.n_main + n_extra, NR, out);
+    if (phases & kAttendPartial) {
+        const dim3 grid((A.n_main + n_extra) * L.rows), block(kThreads);
+        if (L.bf16)
+            SPC_LAUNCH((attend_partial_kernel<BITS, GROUP, G, NROWS, true>), grid, block, stream, L, A);
+        else
+            SPC_LAUNCH((attend_partial_kernel<BITS, GROUP, G, NROWS, false>), grid, block, stream, L, A);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (phases & kAttendCombine)
+        SPC_LAUNCH(attend_combine_kernel, dim3(L.rows * NR), dim3(kCombineThreads), stream, A.part_o, A.part_ml,
+                   A.max_chunks, A.n_main + n_extra, NR, out);
     return hipGetLastError();
 }
 
 template <int BITS, int GROUP>
-hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, float* out, hipStream_t stream) {
+hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, float* out, int phases, hipStream_t stream) {
 #define SPC_CASE(g_, n_)                                                        \
     if (L.G == g_ && n_rows == n_) {                                            \
         A.n_main = (A.Nq + main_chunk(g_ * n_) - 1) / main_chunk(g_ * n_);      \
         const int n_extra = (n_ex + kExtraChunk - 1) / kExtraChunk;             \
         A.n_chunks = A.n_main + n_extra;                                        \
         if (A.n_main + n_extra > A.max_chunks) return hipErrorInvalidValue;     \
-        return launch3<BITS, GROUP, g_, n_>(L, A, n_extra, out, stream);        \
+        return launch3<BITS, GROUP, g_, n_>(L, A, n_extra, out, phases, stream); \
     }
     SPC_CASE(1, 1) SPC_CASE(1, 2) SPC_CASE(2, 1) SPC_CASE(2, 2) SPC_CASE(4, 1) SPC_CASE(4, 2) SPC_CASE(8, 1)
     SPC_CASE(8, 2)
@@ -867,13 +870,16 @@ hipError_t launch2(const LayerView& L, AttendArgs& A, int n_rows, int n_ex, floa
 }  // namespace
 
 int attend_main_chunk_tokens(int NR) { return main_chunk(NR); }
+int attend_chunks(int NR, int Nq, int n_16bit) {
+    return (Nq + main_chunk(NR) - 1) / main_chunk(NR) + (n_16bit + kExtraChunk - 1) / kExtraChunk;
+}
 int attend_extra_chunk_tokens() { return kExtraChunk; }
 int attend_max_chunks() { return kCombineMaxChunks; }
 
 hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
                          const float* logits, size_t logit_stride, const uint16_t* slot, const int32_t* slot_idx,
                          const void* k_spec, const void* v_spec, const AttendScratch& scratch, float* out,
-                         hipStream_t stream) {
+                         int phases, hipStream_t stream) {
     AttendArgs A;
     A.q = (const uint16_t*)q;
     A.logits = logits;
@@ -891,12 +897,12 @@ hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, i
     A.Nq = Nq;
     A.sm_scale = sm_scale;
     const int n_ex = (slot_idx ? L.topk : 0) + (N - Nq) + (k_spec ? 1 : 0);
-    if (L.bits == 2 && L.group == 32) return launch2<2, 32>(L, A, n_rows, n_ex, out, stream);
-    if (L.bits == 2 && L.group == 64) return launch2<2, 64>(L, A, n_rows, n_ex, out, stream);
-    if (L.bits == 1 && L.group == 32) return launch2<1, 32>(L, A, n_rows, n_ex, out, stream);
-    if (L.bits == 1 && L.group == 64) return launch2<1, 64>(L, A, n_rows, n_ex, out, stream);
-    if (L.bits == 2 && L.group == 128) return launch2<2, 128>(L, A, n_rows, n_ex, out, stream);
-    if (L.bits == 1 && L.group == 128) return launch2<1, 128>(L, A, n_rows, n_ex, out, stream);
+    if (L.bits == 2 && L.group == 32) return launch2<2, 32>(L, A, n_rows, n_ex, out, phases, stream);
+    if (L.bits == 2 && L.group == 64) return launch2<2, 64>(L, A, n_rows, n_ex, out, phases, stream);
+    if (L.bits == 1 && L.group == 32) return launch2<1, 32>(L, A, n_rows, n_ex, out, phases, stream);
+    if (L.bits == 1 && L.group == 64) return launch2<1, 64>(L, A, n_rows, n_ex, out, phases, stream);
+    if (L.bits == 2 && L.group == 128) return launch2<2, 128>(L, A, n_rows, n_ex, out, phases, stream);
+    if (L.bits == 1 && L.group == 128) return launch2<1, 128>(L, A, n_rows, n_ex, out, phases, stream);
     return hipErrorInvalidValue;
 }
 

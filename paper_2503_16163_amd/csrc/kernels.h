@@ -104,13 +104,16 @@ struct AttendScratch {
     float* part_ml;  // [rows][max_chunks][NR][2]  (max, sum)
     int max_chunks;
 };
+enum { kAttendPartial = 1, kAttendCombine = 2 };   // which of the two launches launch_attend issues
 int attend_main_chunk_tokens(int NR);
+// chunks the partial pass writes for NR query rows per KV head, Nq quantised and n_16bit 16-bit candidates
+int attend_chunks(int NR, int Nq, int n_16bit);
 int attend_extra_chunk_tokens();
 int attend_max_chunks();   // chunks per row the merge kernel handles
 hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, int Nq, float sm_scale,
                          const float* logits, size_t logit_stride, const uint16_t* slot,
                          const int32_t* slot_idx, const void* k_spec, const void* v_spec,
-                         const AttendScratch& scratch, float* out, hipStream_t stream);
+                         const AttendScratch& scratch, float* out, int phases, hipStream_t stream);
 
 // export: canonical unpacked view of rows' quantised prefix into device buffers
 hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz,

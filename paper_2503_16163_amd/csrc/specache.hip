@@ -466,6 +466,7 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!q || !topk_idx_out) return fail(ctx, SPECACHE_EINVAL, "null q or topk_idx_out");
     if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    if ((uintptr_t)q & 15) return fail(ctx, SPECACHE_EINVAL, "q must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)stream;
     hipStream_t tk = ctx->async_select ? ctx->select_stream : st;   // where ArgTopK runs
@@ -504,6 +505,7 @@ static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n
     if (!ctx->select_on_gather) return fail(ctx, SPECACHE_ESTATE, "specache_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
     if (!q) return fail(ctx, SPECACHE_EINVAL, "null q");
     if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    if ((uintptr_t)q & 15) return fail(ctx, SPECACHE_EINVAL, "q must be 16-byte aligned");
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)stream;
     // the layer's previous selection read L.keys on the stream of the gather that followed it
@@ -526,8 +528,8 @@ static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n
         fused.tail_k = (const uint16_t*)k_new;
         fused.tail_v = (const uint16_t*)v_new;
         fused.tail_N0 = L.N;
-        L.N += 1;
         if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused)) return rc;
+        L.N += 1;   // only once the launch that copies the token is enqueued
     } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) {
         return rc;
     }
@@ -634,8 +636,8 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     return SPECACHE_OK;
 }
 
-int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
-                    const void* v_spec, int32_t slot, float* out, void* stream) {
+static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                       const void* v_spec, int32_t slot, float* out, void* stream) {
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!q || !out) return fail(ctx, SPECACHE_EINVAL, "null q or out");
     if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
@@ -646,14 +648,15 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
         return fail(ctx, SPECACHE_ESTATE, "attend must follow score_topk of the same layer, n_rows and cache state");
     if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
+    const AttendScratch& scratch = ctx->scratch;
     hipStream_t st = (hipStream_t)stream;
     if (slot >= 0 && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
-    {
-        TimedLaunch t(ctx, st, SPECACHE_K_ATTEND);
+    for (int phase : {kAttendPartial, kAttendCombine}) {
+        TimedLaunch t(ctx, st, phase == kAttendPartial ? SPECACHE_K_ATTEND : SPECACHE_K_ATTEND_COMBINE, /*kernel_events=*/true);
         SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
                                    slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
-                                   v_spec, ctx->scratch, out, st));
+                                   v_spec, scratch, out, phase, st));
     }
     if (slot >= 0) {
         L.attend_stream[slot] = st;
@@ -664,6 +667,20 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
             L.attended_recorded[slot] = true;
         }
     }
+    return SPECACHE_OK;
+}
+
+int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                    const void* v_spec, int32_t slot, float* out, void* stream) {
+    return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream);
+}
+
+int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (slot != 0 && slot != 1) return fail(ctx, SPECACHE_EINVAL, "slot must be 0 or 1");
+    Layer& L = ctx->layers[layer];
+    // every 16-bit word becomes 0xFFFF, a NaN in binary16 and in bfloat16
+    SPC_HIP(ctx, hipMemsetAsync(L.slot[slot], 0xFF, (size_t)L.view.rows * ctx->cfg.topk * kRowBytes, (hipStream_t)stream));
     return SPECACHE_OK;
 }
 

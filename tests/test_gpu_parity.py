@@ -633,8 +633,6 @@ def test_error_paths():
         assert ei.value.code == binding.EINVAL
 
 
-# ---- the benchmark's full sizes, in the launch configuration bench.py times; the oracle mirrors a
-# ---- sample of (batch, KV head) rows, all of whose outputs are compared element by element.
 @pytest.mark.timeout(600)
 def test_very_long_row_with_the_largest_k():
     """600000 keys in one row (close to the longest the library takes) and k = 4096, the largest: ArgTopK runs as 16
@@ -652,6 +650,9 @@ def test_very_long_row_with_the_largest_k():
         c.close()
 
 
+# ---- the benchmark's full sizes, one layer, every call on the caller's stream with a host synchronise after
+# ---- every step; the oracle mirrors a sample of distinct (batch, KV head) rows.  The arrangement bench.py times
+# ---- (several layers free-running, side streams, every row compared) is tests/test_gpu_timed_arrangement.py.
 FULL = {
     "config2": dict(B=1, Hq=32, Hkv=32, S=16384, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 0), (0, 13), (0, 31)]),
     "M0_7B_32k": dict(B=1, Hq=32, Hkv=32, S=32768, dtype=synth.FP16, bits=2, g=32, k=256, sample=[(0, 5), (0, 30)]),
