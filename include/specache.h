@@ -240,6 +240,23 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
                     const void* v_spec, int32_t slot, float* out, void* stream);
 
 /*
+ * specache_attend for callers that must not allocate device memory around the call and want
+ * the call's scratch out of the context: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the partial
+ * results of the split over the sequence (rows x chunks x query rows x 130 floats) go to a
+ * 16 MiB array that is part of the library's device image (one copy per GPU, held until the
+ * process ends) instead of the context's scratch buffer.  The call allocates and frees nothing.
+ * Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams, two
+ * contexts) race; calls ordered by one stream do not.  Nothing in the array has to start at
+ * zero (the merge reads only what the partial pass of the same call wrote).
+ * Errors: those of specache_attend; ECAPACITY when the partial results of this call do not fit
+ * the array (nothing is launched; use specache_attend); EHIP when the array's address cannot
+ * be obtained on the current device.
+ */
+int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                           const void* v_spec, int32_t slot, float* out, void* stream);
+
+/*
  * Parity hooks (synchronise the device; all output pointers are host memory and
  * may be NULL to skip that array).
  *

@@ -268,6 +268,31 @@ int gather_phase(specache_ctx* ctx, Layer& L, int Nq, const int32_t* idx, int sl
     return SPECACHE_OK;
 }
 
+// ---- scratch memory for callers that cannot allocate (specache_attend_static) ----------------------
+// A file-scope device array holds the attention partials of such a call.  Every GPU the library
+// runs on carries its own copy at its own address; in host code the array's name is only a handle
+// for hipGetSymbolAddress, never an address to hand to a kernel.  The address is looked up once
+// per device, with that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+float* g_static_scratch[kMaxDevices] = {};
+
+int static_scratch_of_current_device(specache_ctx* ctx, float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(ctx, e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(ctx, SPECACHE_EINVAL, "device ordinal beyond the static scratch table");
+    if (!g_static_scratch[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail_hip(ctx, e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        g_static_scratch[dev] = (float*)ptr;
+    }
+    *out = g_static_scratch[dev];
+    return SPECACHE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -414,6 +439,12 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     }
     SPC_ALLOC(hipDeviceSynchronize());
 #undef SPC_ALLOC
+    {
+        // the static scratch array's address on this device, for specache_attend_static (a failure
+        // here only surfaces when that entry point is called, with its own message)
+        float* unused = nullptr;
+        (void)static_scratch_of_current_device(nullptr, &unused);
+    }
     *out = ctx;
     return SPECACHE_OK;
 }
@@ -636,8 +667,9 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     return SPECACHE_OK;
 }
 
+// specache_attend with the partial results in `scratch`: the context's own, or the static array
 static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
-                       const void* v_spec, int32_t slot, float* out, void* stream) {
+                       const void* v_spec, int32_t slot, float* out, void* stream, const AttendScratch* static_scratch) {
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!q || !out) return fail(ctx, SPECACHE_EINVAL, "null q or out");
     if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
@@ -648,7 +680,19 @@ static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t 
         return fail(ctx, SPECACHE_ESTATE, "attend must follow score_topk of the same layer, n_rows and cache state");
     if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
-    const AttendScratch& scratch = ctx->scratch;
+    AttendScratch scratch = ctx->scratch;
+    if (static_scratch) {
+        // partial outputs [rows][chunks][NR][128] floats, then the (max, sum) pairs [rows][chunks][NR][2]
+        const int NR = L.view.G * n_rows;
+        const int chunks = attend_chunks(NR, L.Nq, (slot >= 0 ? ctx->cfg.topk : 0) + (L.N - L.Nq) + (k_spec ? 1 : 0));
+        const size_t o_floats = (size_t)L.view.rows * chunks * NR * kD, ml_floats = (size_t)L.view.rows * chunks * NR * 2;
+        if ((o_floats + ml_floats) * sizeof(float) > kStaticScratchBytes)
+            return fail(ctx, SPECACHE_ECAPACITY, "specache_attend_static: the partial results of this call (rows x chunks x query rows "
+                                                 "x 130 floats) exceed the 16 MiB static scratch array; use specache_attend");
+        scratch.part_o = static_scratch->part_o;
+        scratch.part_ml = static_scratch->part_o + o_floats;
+        scratch.max_chunks = chunks;
+    }
     hipStream_t st = (hipStream_t)stream;
     if (slot >= 0 && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
@@ -672,7 +716,16 @@ static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t 
 
 int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
                     const void* v_spec, int32_t slot, float* out, void* stream) {
-    return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream);
+    return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, nullptr);
+}
+
+int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                           const void* v_spec, int32_t slot, float* out, void* stream) {
+    if (!ctx) return SPECACHE_EINVAL;
+    float* base = nullptr;
+    if (int rc = static_scratch_of_current_device(ctx, &base)) return rc;
+    const AttendScratch st{base, nullptr, 0};
+    return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, &st);
 }
 
 int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream) {
