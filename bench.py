@@ -119,6 +119,12 @@ def main():
                     help="with ArgTopK on the gather's stream: specache_append_score (the scoring launch carries the copy of "
                          "the new pair) instead of quantize_append and score as two calls.  1 to 3 us per layer faster; off "
                          "by default so that every step of the path keeps a kernel and a timing of its own")
+    ap.add_argument("--one-pass", action="store_true",
+                    help="with ArgTopK on the gather's stream: specache_score_attend (scoring and attention of a chunk in one "
+                         "launch, the logits stay on the chip) instead of specache_score and specache_attend as two calls")
+    ap.add_argument("--vector-alu", default="", choices=["", "score", "attend", "both"],
+                    help="A/B measurement: run the named streaming kernel(s) in the vector-ALU formulation instead of the "
+                         "integer-matrix-core one (one query head per KV head, two rows)")
     ap.add_argument("--hit-rate", action="store_true",
                     help="instead of the timing run: how well the positions selected from the low-bit scores of the "
                          "speculative row match the exact top-k on the 16-bit keys (synthetic stand-in for the "
@@ -136,6 +142,9 @@ def main():
     torch.cuda.set_device(0)
     if args.hit_rate:
         return hit_rate_experiment(torch, binding, synth)
+    if args.vector_alu:
+        binding.debug_kernel_choice({"score": binding.SCORE_ON_VECTOR_ALU, "attend": binding.ATTEND_ON_VECTOR_ALU,
+                                     "both": binding.SCORE_ON_VECTOR_ALU | binding.ATTEND_ON_VECTOR_ALU}[args.vector_alu])
     B, Hq, Hkv, S, dtype, bits, g, k, layers = WORKLOADS[args.workload]
     if args.layers:
         layers = args.layers
@@ -248,6 +257,11 @@ def main():
         slot = (t % 2) if (t > 0 and not args.no_gather) else -1
         for L in range(layers):
             q = q_p[t % nq_pool][L]
+            if async_select == 2 and args.one_pass:
+                sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
+                sc.score_attend(L, q, 2, spec_k_p, spec_v_p, slot, out_p[L], main_h)
+                sc.select_gather(L, idx_p[L][t % 2], (t + 1) % 2 if do_gather else -1, side_h[L % len(side_h)])
+                continue
             if async_select == 2:
                 if not args.fused_append:
                     sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
@@ -312,7 +326,7 @@ def main():
     attend_bytes = packed + B * Hkv * ((k if not args.no_gather else 0) + (N - Nq) + 1) * 512
     layer_bytes = score_bytes + attend_bytes
     us_layer = ms_per_step * 1e3 / layers
-    score_us = per_kernel_us["score"]
+    score_us = per_kernel_us["score"] or per_kernel_us["score_attend"]
     # which scoring kernel the library launches for this shape (two query rows per query head)
     score_name = ("score_i8_kernel" if G == 1 and args.variant != "nonspec"
                   else "score_mfma_kernel" if (G * (1 if args.variant == "nonspec" else 2)) % 8 == 0 else "score_kernel")
@@ -343,9 +357,9 @@ def main():
             roofline["traffic"] = json.load(open(tpath)).get(args.workload, {}).get(score_name)
         except Exception:
             roofline["traffic"] = None
-    attend_us = per_kernel_us["attend"] + (per_kernel_us["attend_combine"] or 0.0)
+    attend_us = (per_kernel_us["attend"] or per_kernel_us["score_attend"]) + (per_kernel_us["attend_combine"] or 0.0)
     breakdown = {n: (round(v, 3) if v is not None else None) for n, v in per_kernel_us.items()}
-    breakdown["score_topk_attend"] = round(sum(per_kernel_us[n] or 0.0 for n in ("score", "topk", "attend", "attend_combine")), 3)
+    breakdown["score_topk_attend"] = round(sum(per_kernel_us[n] or 0.0 for n in ("score", "topk", "attend", "attend_combine", "score_attend")), 3)
     result = {
         "metric": "us per layer decode step (score+top-k+attend) + achieved HBM GB/s, 7B shape 32k ctx"
                   if args.workload == "M0" else "us per layer decode step (score+top-k+attend) + achieved HBM GB/s",

@@ -240,6 +240,24 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
                     const void* v_spec, int32_t slot, float* out, void* stream);
 
 /*
+ * specache_score followed by specache_attend of the same layer, as one call (contexts created
+ * with async_select = SPECACHE_SELECT_STREAM_GATHER; ESTATE otherwise): Appendix A "Decoding",
+ * A = Softmax(Q K^T) on the mixed cache and O = A V, with the low-bit logits of both rows computed
+ * on the way and the speculative row's selection keys left for the following
+ * specache_select_gather (which may be enqueued right after this call: the slot it fills is the
+ * other one).  With one query head per KV head, two query rows, 2-bit codes and selection on the
+ * low-bit logits, one pass over a chunk of 512 positions reads its packed keys, keeps the logits
+ * on the chip, and reads its packed values: the logits never travel to memory and back, and the
+ * layer-step has one launch less.  Every other shape or option runs the two calls one after the
+ * other.  Results are those of the two calls (the attention output to the 2e-3 bar: the softmax
+ * partials are formed per 128 positions instead of per 512); specache_debug_logits afterwards
+ * needs SPECACHE_KEEP_ONE_PASS_LOGITS.  Arguments as in specache_score and specache_attend.
+ * Errors: those of the two calls.
+ */
+int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                          const void* v_spec, int32_t slot, float* out, void* stream);
+
+/*
  * specache_attend for callers that must not allocate device memory around the call and want
  * the call's scratch out of the context: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the partial
@@ -286,6 +304,17 @@ int specache_debug_logits(specache_ctx* ctx, float* out);
 int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream);
 
 /*
+ * Measurement hook, process-wide: which formulation of the two streaming kernels runs for one
+ * query head per KV head and two query rows.  0 (the default): the integer matrix cores; a flag
+ * set: that kernel's vector-ALU formulation instead (same results to the parity bars), so that
+ * the two can be timed and profiled against each other.  Takes effect for calls made afterwards.
+ * Errors: EINVAL (unknown flag).
+ */
+enum { SPECACHE_SCORE_ON_VECTOR_ALU = 1, SPECACHE_ATTEND_ON_VECTOR_ALU = 2,
+       SPECACHE_KEEP_ONE_PASS_LOGITS = 4 /* specache_score_attend also writes its logits out, for specache_debug_logits */ };
+int specache_debug_kernel_choice(int32_t flags);
+
+/*
  * Measurement hook.  While enabled, every hot call brackets each of its kernel
  * phases with a pair of HIP events on the stream the phase is launched on.
  * specache_timing synchronises the device, adds up the elapsed time of all
@@ -304,7 +333,8 @@ enum {
     SPECACHE_K_GATHER = 4,      /* host-link gather (side stream)            */
     SPECACHE_K_ATTEND = 5,      /* mixed attention: partial pass over chunks */
     SPECACHE_K_ATTEND_COMBINE = 6, /* mixed attention: merge of the chunks    */
-    SPECACHE_K_COUNT = 7
+    SPECACHE_K_SCORE_ATTEND = 7, /* scoring and partial pass of specache_score_attend in one launch */
+    SPECACHE_K_COUNT = 8
 };
 int specache_timing(specache_ctx* ctx, int32_t enable, double* total_us, int64_t* launches);
 

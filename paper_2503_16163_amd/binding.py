@@ -18,7 +18,7 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
            "specache_score", "specache_select_gather", "specache_append_score",
-           "specache_attend", "specache_attend_static", "specache_debug_poison_slot", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
+           "specache_attend", "specache_score_attend", "specache_attend_static", "specache_debug_poison_slot", "specache_debug_kernel_choice", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
            "specache_timing", "specache_measure_hbm_read", "specache_measure_link"]
 
 
@@ -65,7 +65,9 @@ def lib():
         L.specache_append_score.argtypes = [vp, i32, vp, vp, vp, i32, vp]
         L.specache_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
         L.specache_attend_static.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
+        L.specache_score_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
         L.specache_debug_poison_slot.argtypes = [vp, i32, i32, vp]
+        L.specache_debug_kernel_choice.argtypes = [i32]
         L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
         L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
         L.specache_debug_logits.argtypes = [vp, vp]
@@ -104,6 +106,16 @@ def plan_append(residual, group, n_tokens, n_quantized, n_new):
     if rc != OK:
         raise SpeCacheError(rc, "plan_append: inconsistent arguments")
     return out.value
+
+
+SCORE_ON_VECTOR_ALU, ATTEND_ON_VECTOR_ALU, KEEP_ONE_PASS_LOGITS = 1, 2, 4
+
+
+def debug_kernel_choice(flags):
+    """Process-wide: send the shapes the integer-matrix-core kernels take to the vector-ALU kernels (A/B timing)."""
+    rc = lib().specache_debug_kernel_choice(flags)
+    if rc != OK:
+        raise SpeCacheError(rc, "debug_kernel_choice: unknown flag")
 
 
 def measure_hbm_read(nbytes=1 << 30, reps=10):
@@ -175,6 +187,10 @@ class SpeCache:
         self._check(lib().specache_attend(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
                                           _ptr(out), _stream(stream)))
 
+    def score_attend(self, layer, q, n_rows, k_spec, v_spec, slot, out, stream=None):
+        self._check(lib().specache_score_attend(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
+                                                _ptr(out), _stream(stream)))
+
     def attend_static(self, layer, q, n_rows, k_spec, v_spec, slot, out, stream=None):
         self._check(lib().specache_attend_static(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,
                                                  _ptr(out), _stream(stream)))
@@ -182,7 +198,7 @@ class SpeCache:
     def debug_poison_slot(self, layer, slot, stream=None):
         self._check(lib().specache_debug_poison_slot(self._ctx, layer, slot, _stream(stream)))
 
-    KERNELS = ("flush", "append_copy", "score", "topk", "gather", "attend", "attend_combine")
+    KERNELS = ("flush", "append_copy", "score", "topk", "gather", "attend", "attend_combine", "score_attend")
 
     def timing(self, enable):
         """Collect and reset per-kernel event timings; returns {kernel: (total_us, launches)}."""

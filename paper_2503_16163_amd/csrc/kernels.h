@@ -115,6 +115,21 @@ hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, i
                          const int32_t* slot_idx, const void* k_spec, const void* v_spec,
                          const AttendScratch& scratch, float* out, int phases, hipStream_t stream);
 
+// the same partial pass for one query head per KV head, two rows, 2-bit values: value side on the integer matrix cores
+bool attend_uses_int8_matrix_cores(const LayerView& L, int n_rows);
+// keys != null: the low-bit scoring runs inside the same launch (logits are not read; the speculative row's
+// selection keys go to keys, and the logits to logits_out if that is set)
+hipError_t launch_attend_i8_partial(const LayerView& L, const void* q, int N, int Nq, float sm_scale, const float* logits,
+                                    size_t logit_stride, const uint16_t* slot, const int32_t* slot_idx, const void* k_spec,
+                                    const void* v_spec, const AttendScratch& scratch, uint32_t* keys, size_t key_stride,
+                                    float* logits_out, hipStream_t stream);
+
+// Process-wide choice of kernels, for A/B measurements of one formulation against the other
+// (specache_debug_kernel_choice): bits set here send the shapes that the matrix-core kernels
+// would take to the vector-ALU kernels instead.
+enum { kChoiceScoreValu = 1, kChoiceAttendValu = 2, kChoiceKeepLogits = 4 };
+int& kernel_choice();
+
 // export: canonical unpacked view of rows' quantised prefix into device buffers
 hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz,
                          uint8_t* v_codes, uint16_t* v_mnmx, float* v_sz, hipStream_t stream);

@@ -287,7 +287,7 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
     if (L.group != 32 && L.group != 64 && L.group != 128) return hipErrorInvalidValue;
     // two rows of one query head: the integer matrix cores take the contraction (it reads q 16 bytes at a
     // time; the C ABI rejects a q that is not 16-byte aligned)
-    if (score_uses_int8_matrix_cores(L.G, n_rows))
+    if (score_uses_int8_matrix_cores(L.G, n_rows) && !(kernel_choice() & kChoiceScoreValu))
         return launch_score_i8(L, q, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);
     if (score_uses_matrix_cores(L.G, n_rows))
         return launch_score_mfma(L, q, n_rows, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);

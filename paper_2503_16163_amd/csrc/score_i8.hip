@@ -43,52 +43,12 @@
 // waves that walk several tiles with the next tile's loads in flight (15.4 - 18.3 us: fewer
 // waves, more registers), padding against LDS bank conflicts, and leaving out the key array
 // (ArgTopK ranking the logits costs it more than the store saves here).
-#include "kernels.h"
-#include "layout.h"
+#include "score_i8_wave.h"
 
 namespace specache {
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-constexpr int kWaves = 4;
-constexpr int kPieceStride = 36;                          // dwords: 32 channel quads of one byte plane + pad
-constexpr int kSubStride = 2 * 4 * kPieceStride + 8;      // dwords: [row][byte plane] of one sub-group + pad
-constexpr int kWaveDwords = 4 * kSubStride;
-constexpr int kResBlock = 64 + 4;                         // dwords between the result blocks of (sub-group, row, half)
-static_assert(kWaveDwords >= 16 * kResBlock, "the result exchange reuses the multiplier area");
-
-// lane exchange patterns inside a row of 16 lanes
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
-__device__ __forceinline__ float row16_max(float v) {
-    v = fmaxf(v, dpp_move<kDppXor1>(v));
-    v = fmaxf(v, dpp_move<kDppXor2>(v));
-    v = fmaxf(v, dpp_move<kDppHalfMirror>(v));
-    return fmaxf(v, dpp_move<kDppMirror>(v));
-}
-__device__ __forceinline__ float row16_sum(float v) {
-    v += dpp_move<kDppXor1>(v);
-    v += dpp_move<kDppXor2>(v);
-    v += dpp_move<kDppHalfMirror>(v);
-    return v + dpp_move<kDppMirror>(v);
-}
-
-__device__ __forceinline__ uint32_t comp(const uint4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
-
-// bytes p = 0..3 of four 32-bit words, gathered per byte position: out[p] = (y0.p, y1.p, y2.p, y3.p)
-__device__ __forceinline__ void byte_planes(uint32_t y0, uint32_t y1, uint32_t y2, uint32_t y3, uint32_t out[4]) {
-    const uint32_t a_lo = __builtin_amdgcn_perm(y1, y0, 0x05010400u), a_hi = __builtin_amdgcn_perm(y1, y0, 0x07030602u);
-    const uint32_t b_lo = __builtin_amdgcn_perm(y3, y2, 0x05010400u), b_hi = __builtin_amdgcn_perm(y3, y2, 0x07030602u);
-    out[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
-    out[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
-    out[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
-    out[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
-}
+constexpr int kWaves = kI8Waves;
 
 template <int BITS, bool BF16>
 // at most 64 registers: all eight waves a SIMD gets are resident at once
@@ -96,8 +56,6 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(8, 
                                                                float sm_scale, float* __restrict__ logits,
                                                                size_t logit_stride, uint32_t* __restrict__ keys,
                                                                size_t key_stride) {
-    constexpr int NW = 4 * BITS;               // code dwords per token
-    constexpr int LD = NW / 4;                 // code dwords a lane quarter loads per token: 2 (2-bit) or 1 (1-bit)
     __shared__ __attribute__((aligned(16))) uint32_t xch[kWaves][kWaveDwords];
     __shared__ __attribute__((aligned(8))) float2 fin[kWaves][4][2];   // (scale back, zero-point sum) per (sub-group, row)
 
@@ -108,155 +66,9 @@ __global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(8, 
     const int sub0 = tile * 16 + 4 * wave;                     // this wave's first sub-group
     if (sub0 >= n_sub) return;                                 // the waves never meet at a barrier
 
-    // ---- code dwords, requested first -----------------------------------------------------
-    // lane = (MFMA row rA, channel quarter qd); row rA is layout lane 16 wave + rA of the tile.
-    const int rA = lane & 15, qd = lane >> 4;
-    int lam = 16 * wave + rA;
-    if (tile * 16 + lam / 4 >= n_sub) lam = ((n_sub - 1) % 16) * 4 + (lam & 3);   // past the end: a valid sub-group again
-    const uint8_t* kc_lane = L.kc + (size_t)row * L.kc_stride + (size_t)tile * k_tile_bytes(BITS) + (size_t)lam * 16;
-    uint4 cw[LD][2];
-#pragma unroll
-    for (int i = 0; i < LD; ++i)
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-            cw[i][hf] = *reinterpret_cast<const uint4*>(kc_lane + (size_t)((4 * i + qd) * 2 + hf) * 1024);
-
-    // ---- multipliers: lane (sub-group sgP, u) folds channel quads 2u and 2u + 1 of that sub-group
-    const int sgP = lane >> 4, u = lane & 15;
-    const int subP = sub0 + sgP < n_sub ? sub0 + sgP : n_sub - 1;
-    const int group_of_sub = subP * kBlockTokens / L.group;     // the sub-groups of one token group share its metadata
-    const uint32_t* km_p = L.km + (size_t)row * L.km_stride + (size_t)group_of_sub * kD + 2 * u;
-    uint2 mt[4];                                               // (min, max) of channels 4 (2u + mq) + b, mq = .x/.y
-#pragma unroll
-    for (int b = 0; b < 4; ++b) mt[b] = *reinterpret_cast<const uint2*>(km_p + b * 32);
-    uint4 qraw[2];                                             // channels 8u .. 8u + 7 of both rows
-#pragma unroll
-    for (int r = 0; r < 2; ++r) qraw[r] = *reinterpret_cast<const uint4*>(q + ((size_t)row * 2 + r) * kD + 8 * u);
-
-    float x[2][8], qz[2] = {0.0f, 0.0f}, mx[2] = {0.0f, 0.0f};
-#pragma unroll
-    for (int mq = 0; mq < 2; ++mq)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const uint32_t m = mq ? mt[b].y : mt[b].x;
-            float sc, z;
-            derive_scale_zero<BITS>(widen16<BF16>(m & 0xFFFFu), widen16<BF16>(m >> 16), L.one_bit_plain, sc, z);
-            const int e = 4 * mq + b;
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const uint32_t pair = comp(qraw[r], e / 2);
-                const float qv = widen16<BF16>((e & 1) ? pair >> 16 : pair & 0xFFFFu) * sm_scale;
-                x[r][e] = qv * sc;
-                qz[r] = __builtin_fmaf(qv, z, qz[r]);
-                mx[r] = fmaxf(mx[r], fabsf(x[r][e]));
-            }
-        }
-    // the factor by which the codes of a channel quad arrive multiplied: 4^(quad % 2) for 2-bit
-    // codes, 2^(quad % 4) for 1-bit codes
-    float cls[2];
-    if constexpr (BITS == 2) {
-        cls[0] = 1.0f;
-        cls[1] = 0.25f;
-    } else {
-        cls[0] = (u & 1) ? 0.25f : 1.0f;
-        cls[1] = (u & 1) ? 0.125f : 0.5f;
-    }
-    uint32_t* area = xch[wave];
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const float top = row16_max(mx[r]);
-        qz[r] = row16_sum(qz[r]);
-        // top < 2^(E - 126) with E its exponent field: x * 2^(156 - E) stays below 2^30
-        uint32_t E = __float_as_uint(top) >> 23;
-        E = E < 30u ? 30u : (E > 254u ? 254u : E);
-        const float up = __uint_as_float((283u - E) << 23);
-        if (u == 0) fin[wave][sgP][r] = make_float2(__uint_as_float((E - 29u) << 23), qz[r]);
-        const float up_c[2] = {up * cls[0], up * cls[1]};
-#pragma unroll
-        for (int mq = 0; mq < 2; ++mq) {
-            uint32_t y[4], planes[4];
-#pragma unroll
-            for (int b = 0; b < 4; ++b)
-                y[b] = ((uint32_t)(int)(x[r][4 * mq + b] * up_c[mq]) + 0x00808080u) ^ 0x00808080u;
-            byte_planes(y[0], y[1], y[2], y[3], planes);
-#pragma unroll
-            for (int pp = 0; pp < 4; ++pp) area[sgP * kSubStride + (r * 4 + pp) * kPieceStride + 2 * u + mq] = planes[pp];
-        }
-    }
-    // The lanes of a wave run in lockstep and LDS serves one wave's accesses in order: a
-    // wave-level fence is all the exchange needs.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // B operands of this lane: column (sub-group sgB, byte p), channel quarter qd; the 16 k-slots
-    // of step ks are channel quads m0 .. m0 + 3 in the order the masked code bytes have
-    const int sgB = (lane & 15) >> 2, p = lane & 3;
-    v4i bop[2][2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        const int m0 = BITS == 2 ? 16 * ks + 4 * qd : 8 * qd + 4 * ks;
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-            bop[ks][r] = *reinterpret_cast<const v4i*>(area + sgB * kSubStride + (r * 4 + p) * kPieceStride + m0);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();                 // every lane has read its B operands: the area is free
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // ---- the contraction: per token (half hf, j of the lane's four) two k-steps, two rows.
-    // Result register v of lane (column n, quarter qq) is MFMA row 4 qq + v: sub-group qq of the
-    // wave, quad lane v, i.e. token 32 (sub0 + qq) + 8 v + 4 hf + j.  It is wanted where the
-    // column's sub-group is qq too; those quads go to block (sub-group, row, hf) of the area as
-    // [byte p][token j][quad lane v], the blocks 4 dwords further apart than their size so that
-    // the lanes that read one position of 16 different blocks hit 16 different banks.
-#pragma unroll
-    for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            v4i acc[2];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                v4i a;
-                if constexpr (BITS == 2) {
-                    const uint32_t w = comp(cw[ks][hf], j), t = w >> 4;
-                    a = (v4i){(int)(w & 0x03030303u), (int)(w & 0x0C0C0C0Cu), (int)(t & 0x03030303u), (int)(t & 0x0C0C0C0Cu)};
-                } else {
-                    const uint32_t t = comp(cw[0][hf], j) >> (4 * ks);
-                    a = (v4i){(int)(t & 0x01010101u), (int)(t & 0x02020202u), (int)(t & 0x04040404u), (int)(t & 0x08080808u)};
-                }
-#pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    acc[r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bop[ks][r], ks == 0 ? (v4i){0, 0, 0, 0} : acc[r], 0, 0, 0);
-            }
-            if (sgB == qd) {
-#pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    *reinterpret_cast<v4i*>(area + ((qd * 2 + r) * 2 + hf) * kResBlock + (p * 4 + j) * 4) = acc[r];
-            }
-        }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-    // ---- every lane finishes four consecutive tokens of one row: lane = (sub-group sgO, row rO,
-    // ---- quad lane vO, half hfO), 8 lanes cover the 32 tokens of a sub-group in order
-    const int sgO = lane >> 4, rO = (lane >> 3) & 1, vO = (lane >> 1) & 3, hfO = lane & 1;
-    int s[4][4];   // [byte p][token j]
-    const uint32_t* blk = area + ((sgO * 2 + rO) * 2 + hfO) * kResBlock + vO;
-#pragma unroll
-    for (int pp = 0; pp < 4; ++pp)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s[pp][j] = (int)blk[(pp * 4 + j) * 4];
-    const float2 f = fin[wave][sgO][rO];
     float o[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float t = __builtin_fmaf((float)s[1][j], 256.0f, (float)s[0][j]);
-        t = __builtin_fmaf((float)s[2][j], 65536.0f, t);
-        t = __builtin_fmaf((float)s[3][j], 16777216.0f, t);
-        o[j] = __builtin_fmaf(t, f.x, f.y);
-    }
+    score_i8_wave<BITS, BF16>(L, q, row, tile, wave, lane, n_sub, sm_scale, xch[wave], fin[wave], o);
+    const int sgO = lane >> 4, rO = (lane >> 3) & 1, vO = (lane >> 1) & 3, hfO = lane & 1;
     if (sub0 + sgO < n_sub) {
         const size_t i4 = (size_t)(sub0 + sgO) * kBlockTokens + 8 * vO + 4 * hfO;
         *reinterpret_cast<float4*>(logits + ((size_t)row * 2 + rO) * logit_stride + i4) = make_float4(o[0], o[1], o[2], o[3]);

@@ -22,6 +22,10 @@ LaunchEvents& pending_launch_events() {
     static thread_local LaunchEvents le;
     return le;
 }
+int& kernel_choice() {
+    static int choice = 0;
+    return choice;
+}
 }  // namespace specache
 
 namespace {
@@ -82,6 +86,7 @@ struct specache_ctx {
     AttendScratch scratch{};
     TopkScratch topk_scratch{};
     int scored_layer = -1, scored_rows = 0, scored_N = 0, scored_Nq = 0;
+    bool logits_kept = false;    // the last scoring pass left its logits in `logits` (the one-pass score + attend need not)
     uint64_t seq = 0;            // counts the calls that order streams (see Layer)
     hipStream_t last_gather_stream = nullptr;   // stream of the previous specache_gather, of any layer
     bool last_gather_stream_set = false;
@@ -526,19 +531,12 @@ int specache_score_topk(specache_ctx* ctx, int32_t layer, const void* q, int32_t
     ctx->scored_rows = n_rows;
     ctx->scored_N = L.N;
     ctx->scored_Nq = L.Nq;
+    ctx->logits_kept = true;
     return SPECACHE_OK;
 }
 
-// specache_score, optionally with the copy of one new token carried by the scoring launch
-static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream, const void* k_new,
-                      const void* v_new) {
-    if (int rc = check_ctx_layer(ctx, layer)) return rc;
-    if (!ctx->select_on_gather) return fail(ctx, SPECACHE_ESTATE, "specache_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
-    if (!q) return fail(ctx, SPECACHE_EINVAL, "null q");
-    if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
-    if ((uintptr_t)q & 15) return fail(ctx, SPECACHE_EINVAL, "q must be 16-byte aligned");
-    Layer& L = ctx->layers[layer];
-    hipStream_t st = (hipStream_t)stream;
+// The layer's key array is about to be rewritten on st: the selections that read it come first.
+static int wait_for_keys_readers(specache_ctx* ctx, Layer& L, hipStream_t st) {
     // the layer's previous selection read L.keys on the stream of the gather that followed it
     if (L.keys_reader_slot >= 0) {
         const int sl = L.keys_reader_slot;
@@ -553,18 +551,11 @@ static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n
         if (L.selected_stream != st) SPC_HIP(ctx, hipStreamWaitEvent(st, L.selected, 0));
         L.selected_pending = false;
     }
-    if (k_new) {
-        // the scoring launch appends token N: one more workgroup per row copies the pair
-        LayerView fused = L.view;
-        fused.tail_k = (const uint16_t*)k_new;
-        fused.tail_v = (const uint16_t*)v_new;
-        fused.tail_N0 = L.N;
-        if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused)) return rc;
-        L.N += 1;   // only once the launch that copies the token is enqueued
-    } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) {
-        return rc;
-    }
-    // "scored": what the selection waits for, and what orders a gather after the attends enqueued so far
+    return SPECACHE_OK;
+}
+
+// "scored": what the selection waits for, and what orders a gather after the attends enqueued so far
+static int record_scored(specache_ctx* ctx, Layer& L, int32_t layer, int32_t n_rows, hipStream_t st) {
     SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;
     L.idx_ready_stream = st;
@@ -577,6 +568,32 @@ static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n
     ctx->scored_N = L.N;
     ctx->scored_Nq = L.Nq;
     return SPECACHE_OK;
+}
+
+// specache_score, optionally with the copy of one new token carried by the scoring launch
+static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream, const void* k_new,
+                      const void* v_new) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!ctx->select_on_gather) return fail(ctx, SPECACHE_ESTATE, "specache_score needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    if (!q) return fail(ctx, SPECACHE_EINVAL, "null q");
+    if (n_rows != 1 && n_rows != 2) return fail(ctx, SPECACHE_EINVAL, "n_rows must be 1 or 2");
+    if ((uintptr_t)q & 15) return fail(ctx, SPECACHE_EINVAL, "q must be 16-byte aligned");
+    Layer& L = ctx->layers[layer];
+    hipStream_t st = (hipStream_t)stream;
+    if (int rc = wait_for_keys_readers(ctx, L, st)) return rc;
+    if (k_new) {
+        // the scoring launch appends token N: one more workgroup per row copies the pair
+        LayerView fused = L.view;
+        fused.tail_k = (const uint16_t*)k_new;
+        fused.tail_v = (const uint16_t*)v_new;
+        fused.tail_N0 = L.N;
+        if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused)) return rc;
+        L.N += 1;   // only once the launch that copies the token is enqueued
+    } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) {
+        return rc;
+    }
+    ctx->logits_kept = true;
+    return record_scored(ctx, L, layer, n_rows, st);
 }
 
 int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream) {
@@ -667,6 +684,20 @@ int specache_gather(specache_ctx* ctx, int32_t layer, const int32_t* idx, int32_
     return SPECACHE_OK;
 }
 
+// the attention kernels that read `slot` are enqueued on st: remember it for the slot's next gather
+static int record_attended(specache_ctx* ctx, Layer& L, int slot, hipStream_t st) {
+    if (slot >= 0) {
+        L.attend_stream[slot] = st;
+        L.attend_seq[slot] = ++ctx->seq;
+        L.attended_recorded[slot] = false;
+        if (!(L.idx_ready_recorded && st == L.select_origin_stream)) {
+            SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
+            L.attended_recorded[slot] = true;
+        }
+    }
+    return SPECACHE_OK;
+}
+
 // specache_attend with the partial results in `scratch`: the context's own, or the static array
 static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
                        const void* v_spec, int32_t slot, float* out, void* stream, const AttendScratch* static_scratch) {
@@ -678,6 +709,7 @@ static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t 
     Layer& L = ctx->layers[layer];
     if (ctx->scored_layer != layer || ctx->scored_rows != n_rows || ctx->scored_N != L.N || ctx->scored_Nq != L.Nq)
         return fail(ctx, SPECACHE_ESTATE, "attend must follow score_topk of the same layer, n_rows and cache state");
+    if (!ctx->logits_kept) return fail(ctx, SPECACHE_ESTATE, "the last scoring pass of this layer was specache_score_attend, which keeps no logits");
     if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
     if (L.N == 0 && !k_spec) return fail(ctx, SPECACHE_ESTATE, "no attention candidate");
     AttendScratch scratch = ctx->scratch;
@@ -702,21 +734,52 @@ static int attend_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t 
                                    slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
                                    v_spec, scratch, out, phase, st));
     }
-    if (slot >= 0) {
-        L.attend_stream[slot] = st;
-        L.attend_seq[slot] = ++ctx->seq;
-        L.attended_recorded[slot] = false;
-        if (!(L.idx_ready_recorded && st == L.select_origin_stream)) {
-            SPC_HIP(ctx, hipEventRecord(L.attended[slot], st));
-            L.attended_recorded[slot] = true;
-        }
-    }
-    return SPECACHE_OK;
+    return record_attended(ctx, L, slot, st);
 }
 
 int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
                     const void* v_spec, int32_t slot, float* out, void* stream) {
     return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, nullptr);
+}
+
+int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                          const void* v_spec, int32_t slot, float* out, void* stream) {
+    if (int rc = check_ctx_layer(ctx, layer)) return rc;
+    if (!ctx->select_on_gather)
+        return fail(ctx, SPECACHE_ESTATE, "specache_score_attend needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    Layer& L = ctx->layers[layer];
+    const bool one_pass = L.view.G == 1 && n_rows == 2 && attend_uses_int8_matrix_cores(L.view, n_rows) && L.Nq > 0 &&
+                          ctx->cfg.select_cache == SPECACHE_SELECT_LOWBIT && q && out && !((uintptr_t)q & 15) &&
+                          !(kernel_choice() & (kChoiceScoreValu | kChoiceAttendValu));
+    if (!one_pass) {
+        // other shapes and options: the two passes one after the other, same results
+        if (int rc = score_impl(ctx, layer, q, n_rows, stream, nullptr, nullptr)) return rc;
+        return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, nullptr);
+    }
+    if ((k_spec == nullptr) != (v_spec == nullptr)) return fail(ctx, SPECACHE_EINVAL, "k_spec and v_spec must both be given or both be null");
+    if (slot < -1 || slot > 1) return fail(ctx, SPECACHE_EINVAL, "slot must be -1, 0 or 1");
+    if (slot >= 0 && !L.slot_filled[slot]) return fail(ctx, SPECACHE_ESTATE, "slot was never gathered");
+    hipStream_t st = (hipStream_t)stream;
+    if (int rc = wait_for_keys_readers(ctx, L, st)) return rc;
+    if (slot >= 0 && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
+        SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
+    const bool keep = (kernel_choice() & kChoiceKeepLogits) != 0;
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_SCORE_ATTEND, /*kernel_events=*/true);
+        SPC_HIP(ctx, launch_attend_i8_partial(L.view, q, L.N, L.Nq, ctx->sm_scale, nullptr, ctx->logit_stride,
+                                              slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
+                                              v_spec, ctx->scratch, L.keys, ctx->logit_stride, keep ? ctx->logits : nullptr, st));
+    }
+    ctx->logits_kept = keep;
+    // the keys are complete here: the selection on the side stream can start while the chunks are merged
+    if (int rc = record_scored(ctx, L, layer, n_rows, st)) return rc;
+    {
+        TimedLaunch t(ctx, st, SPECACHE_K_ATTEND_COMBINE, /*kernel_events=*/true);
+        SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
+                                   slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec, v_spec,
+                                   ctx->scratch, out, kAttendCombine, st));
+    }
+    return record_attended(ctx, L, slot, st);
 }
 
 int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
@@ -726,6 +789,15 @@ int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int3
     if (int rc = static_scratch_of_current_device(ctx, &base)) return rc;
     const AttendScratch st{base, nullptr, 0};
     return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, &st);
+}
+
+int specache_debug_kernel_choice(int32_t flags) {
+    if (flags < 0 || flags > (SPECACHE_SCORE_ON_VECTOR_ALU | SPECACHE_ATTEND_ON_VECTOR_ALU | SPECACHE_KEEP_ONE_PASS_LOGITS))
+        return SPECACHE_EINVAL;
+    kernel_choice() = (flags & SPECACHE_SCORE_ON_VECTOR_ALU ? kChoiceScoreValu : 0) |
+                      (flags & SPECACHE_ATTEND_ON_VECTOR_ALU ? kChoiceAttendValu : 0) |
+                      (flags & SPECACHE_KEEP_ONE_PASS_LOGITS ? kChoiceKeepLogits : 0);
+    return SPECACHE_OK;
 }
 
 int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream) {
@@ -800,6 +872,7 @@ int specache_timing(specache_ctx* ctx, int32_t enable, double* total_us, int64_t
 int specache_debug_logits(specache_ctx* ctx, float* out) {
     if (!ctx || !out) return SPECACHE_EINVAL;
     if (ctx->scored_layer < 0) return fail(ctx, SPECACHE_ESTATE, "nothing scored yet");
+    if (!ctx->logits_kept) return fail(ctx, SPECACHE_ESTATE, "specache_score_attend kept no logits (see specache_debug_kernel_choice)");
     SPC_HIP(ctx, hipDeviceSynchronize());
     const size_t n = (size_t)ctx->layers[ctx->scored_layer].view.rows * ctx->layers[ctx->scored_layer].view.G * ctx->scored_rows;
     const size_t Nq = ctx->scored_Nq;

@@ -64,7 +64,7 @@ class Case:
 
     def __init__(self, B, Hq, Hkv, S, dtype, bits, g, k, R=64, seed=1000, n_rows=2, sample=None,
                  max_seq=None, n_outlier=4, one_bit_form=0, select_form=0, select_cache=0, async_select=0,
-                 fused_append=False):
+                 fused_append=False, one_pass=False):
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k, self.R = B, Hq, Hkv, S, dtype, bits, g, k, R
         self.seed, self.n_rows, self.G, self.D = seed, n_rows, Hq // Hkv, 128
         self.sm_scale = 1.0 / np.sqrt(128.0)
@@ -73,6 +73,7 @@ class Case:
         self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
         self.async_select = async_select
         self.fused_append = bool(fused_append) and async_select == 2   # specache_append_score in decode_step
+        self.one_pass = bool(one_pass) and async_select == 2           # specache_score_attend in decode_step
         self.pending = None
         self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
         self.sc = binding.SpeCache(1, B, Hq, Hkv, bits, g, cap, k, dtype, residual=R, one_bit_form=one_bit_form,
@@ -165,7 +166,13 @@ class Case:
         ks, vs = (to_dev(ks_bits, self.dtype), to_dev(vs_bits, self.dtype)) if use_spec else (None, None)
         idx = self.idx[t % 2]
         main = torch.cuda.current_stream()
-        if self.async_select == 2:   # ArgTopK on the gather's stream: the other pair of calls
+        out = torch.empty((self.B, self.Hq, nr, self.D), dtype=torch.float32, device="cuda")
+        slot = (t % 2) if (t > 0 and do_gather) else -1
+        if self.one_pass:            # scoring and attention in one call, then the selection and the gather
+            self._flush_pending()
+            self.sc.score_attend(0, q, nr, ks, vs, slot, out, main)
+            self.sc.select_gather(0, idx, (t + 1) % 2 if do_gather else -1, self.side)
+        elif self.async_select == 2:   # ArgTopK on the gather's stream: the other pair of calls
             if self.pending is not None:
                 self.sc.append_score(0, self.pending[0], self.pending[1], q, nr, main)
                 self.pending = None
@@ -176,9 +183,8 @@ class Case:
             self.sc.score_topk(0, q, nr, idx, main)
             if do_gather:
                 self.sc.gather(0, idx, (t + 1) % 2, self.side)
-        out = torch.empty((self.B, self.Hq, nr, self.D), dtype=torch.float32, device="cuda")
-        slot = (t % 2) if (t > 0 and do_gather) else -1
-        self.sc.attend(0, q, nr, ks, vs, slot, out, main)
+        if not self.one_pass:
+            self.sc.attend(0, q, nr, ks, vs, slot, out, main)
         torch.cuda.synchronize()
         idx_h = idx.cpu().numpy()
         out_h = out.cpu().numpy()

@@ -452,6 +452,71 @@ def test_append_carried_by_the_scoring_launch(Hq, Hkv, dtype, bits, g, R):
         c.close()
 
 
+@pytest.mark.parametrize("Hq,Hkv,S,dtype,bits,g,R,k", [
+    (2, 2, 1700, synth.FP16, 2, 32, 64, 48),        # ragged tail: 1664 quantised positions = 3 chunks and a quarter
+    (3, 3, 2100, synth.BF16, 2, 64, 64, 300),       # g = 64: one value group per channel set
+    (2, 2, 1300, synth.FP16, 2, 128, 128, 40),      # g = 128: one value group per token
+    (1, 1, 90, synth.BF16, 2, 32, 64, 16),          # 32 quantised positions: one wave of one chunk, three empty waves
+    (2, 2, 5000, synth.FP16, 2, 32, 64, 700),       # index list longer than a wave walks: the workgroup-wide bitmap
+    (4, 2, 1500, synth.FP16, 2, 32, 64, 32),        # two query heads per KV head: the two calls one after the other
+    (2, 2, 1500, synth.BF16, 1, 32, 64, 32),        # 1-bit codes: likewise
+])
+def test_scoring_and_attention_in_one_pass(Hq, Hkv, S, dtype, bits, g, R, k):
+    """specache_score_attend: one launch scores a chunk's packed keys, keeps the logits on the chip and reads the
+    chunk's packed values (one query head per KV head, two rows, 2-bit codes); other shapes run the two calls.
+    40 decode steps across flushes; every step's selection, logits (kept on request) and output against the oracle."""
+    from tests.harness import Case
+    binding.debug_kernel_choice(binding.KEEP_ONE_PASS_LOGITS)
+    c = Case(1, Hq, Hkv, S, dtype, bits, g, k, R=R, seed=3600 + Hq + g + bits, async_select=2, one_pass=True)
+    try:
+        c.load()
+        c.decode_step()                      # nothing staged yet (slot -1)
+        for t in range(40):
+            c.append_token(t)
+            c.decode_step(check_logits=(t % 8 == 0))
+        c.check_quantized()
+        print(c.stats)
+    finally:
+        c.close()
+        binding.debug_kernel_choice(0)
+    # without the request the logits are not kept, and the plain attend says so
+    c = Case(1, 2, 2, 700, synth.FP16, 2, 32, 24, seed=3650, async_select=2, one_pass=True)
+    try:
+        c.load()
+        c.decode_step(check_logits=False)
+        with pytest.raises(binding.SpeCacheError) as ei:
+            c.sc.debug_logits(0, 2)
+        assert ei.value.code == binding.ESTATE
+        q = torch.zeros((1, 2, 2, 128), dtype=torch.float16, device="cuda")
+        out = torch.zeros((1, 2, 2, 128), dtype=torch.float32, device="cuda")
+        with pytest.raises(binding.SpeCacheError) as ei:
+            c.sc.attend(0, q, 2, None, None, -1, out)
+        assert ei.value.code == binding.ESTATE
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("what", ["score", "attend", "both"])
+def test_vector_alu_formulations_still_match(what):
+    """The vector-ALU kernels that the integer-matrix-core kernels replaced for one query head per KV head and two
+    rows stay reachable (A/B measurements): same parity bars."""
+    from tests.harness import Case
+    binding.debug_kernel_choice({"score": binding.SCORE_ON_VECTOR_ALU, "attend": binding.ATTEND_ON_VECTOR_ALU,
+                                 "both": binding.SCORE_ON_VECTOR_ALU | binding.ATTEND_ON_VECTOR_ALU}[what])
+    try:
+        for (dtype, bits, g) in ((synth.FP16, 2, 32), (synth.BF16, 2, 64)):
+            c = Case(1, 2, 2, 1700, dtype, bits, g, 48, seed=3700 + g)
+            try:
+                c.load()
+                for t in range(3):
+                    c.append_token(t)
+                    c.decode_step()
+            finally:
+                c.close()
+    finally:
+        binding.debug_kernel_choice(0)
+
+
 def test_repeated_selection_and_slot_refill_across_streams():
     """Call sequences a stepping loop does not produce, which the library still has to order: the same keys
     selected twice, on two side streams, into both slots; a slot refilled from another stream than its last

@@ -47,14 +47,17 @@ def _same_rows(a, what):
     assert not bad, f"{what}: rows {bad[:8]} differ from row 0"
 
 
-def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=None, arrange=None):
+def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=None, arrange=None, one_pass=False):
     from oracle import oracle as orc
     from tests.harness import OUT_TOL, check_out, check_topk
     B, Hq, Hkv, S, dtype, bits, g, k, layers = shape or SHAPES[name]
     G, D, R = Hq // Hkv, 128, max(64, g)
     seed = 5000 + S + k
     async_select, n_side = arrange or arrangement.pick(G, S, k, layers)
-    if fused_append:
+    if one_pass and shape is None:
+        async_select = 2          # specache_score_attend leaves its keys to specache_select_gather
+        n_side = arrangement.side_streams(async_select, G, S, k)
+    if fused_append or one_pass:
         assert async_select == 2
     max_seq = ((S + steps + 63) // 64 + 1) * 64
     sc = binding.SpeCache(layers, B, Hq, Hkv, bits, g, max_seq, k, dtype, residual=R, async_select=async_select)
@@ -105,7 +108,11 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
             slot = (t % 2) if t > 0 else -1
             for L in range(layers):
                 side = sides[L % n_side]
-                if async_select == 2:
+                if one_pass:
+                    sc.quantize_append(L, nkd, nvd, 1, main)
+                    sc.score_attend(L, q, 2, ks, vs, slot, out[L][t], main)
+                    sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, side)
+                elif async_select == 2:
                     if fused_append:
                         sc.append_score(L, nkd, nvd, q, 2, main)
                     else:
@@ -118,7 +125,8 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
                     sc.gather(L, idx[L][t % 2], (t + 1) % 2, side)
                 with torch.cuda.stream(side):        # behind the gather, which is behind the selection
                     idx_kept[L][t].copy_(idx[L][t % 2], non_blocking=True)
-                sc.attend(L, q, 2, ks, vs, slot, out[L][t], main)
+                if not one_pass:
+                    sc.attend(L, q, 2, ks, vs, slot, out[L][t], main)
                 if poison and slot >= 0:
                     # whatever reads this slot before the next gather has rewritten it now reads NaNs
                     sc.debug_poison_slot(L, slot, main)
@@ -169,6 +177,17 @@ def test_full_size_fused_append_in_the_timed_arrangement():
     run_free_running("M0_7B_32k", fused_append=True)
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["config1", "config2", "M0_7B_32k", "config3", "config4"])
+def test_full_size_all_rows_scoring_and_attention_in_one_pass(name):
+    """The same with specache_score_attend in place of specache_score + specache_attend (configs 1 to 3 and the 7B
+    shape run the one-pass kernel; config 4, with four query heads per KV head, the two passes behind the one call)."""
+    if name == "config1":
+        run_free_running(name, one_pass=True, shape=SHAPES[name], arrange=(2, 2))
+    else:
+        run_free_running(name, one_pass=True)
+
+
 @pytest.mark.parametrize("async_select,n_side", [(0, 2), (1, 2), (2, 2), (2, 3)])
 def test_poisoned_staging_slots_show_no_read_before_gather(async_select, n_side):
     """The one race surface of the path is the pair of staging slots that a side stream fills while the main
@@ -180,6 +199,9 @@ def test_poisoned_staging_slots_show_no_read_before_gather(async_select, n_side)
     run_free_running("poison", poison=True, steps=12, shape=shape, arrange=(async_select, n_side))
     shape = (1, 8, 2, 1500, synth.BF16, 1, 32, 40, 3)
     run_free_running("poison-gqa", poison=True, steps=6, shape=shape, arrange=(async_select, n_side))
+    if async_select == 2:
+        shape = (2, 4, 4, 2300, synth.FP16, 2, 32, 72, 3)
+        run_free_running("poison-one-pass", poison=True, steps=12, shape=shape, arrange=(async_select, n_side), one_pass=True)
 
 
 def test_misaligned_query_is_an_error():
