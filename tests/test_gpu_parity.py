@@ -105,6 +105,48 @@ def test_long_row_topk_in_two_launches_keeps_the_tie_rule():
         c.close()
 
 
+@pytest.mark.parametrize("case", ["ties_top_class", "ties_second_class", "all_equal", "crowded", "gqa", "one_row_short"])
+def test_topk_on_structured_scores(case):
+    """ArgTopK on score patterns that stress the radix select and its tie rule: keys that repeat with period 32
+    (32 classes of exactly equal scores: the boundary falls inside the top class, whose lowest positions have to
+    win); period 64 with the boundary in the second class, in a row long enough for the two-launch selection;
+    all keys equal; 1200 large keys crowded into 38 consecutive sub-groups of 32; four query heads per KV head
+    with 1-bit codes; and one short row."""
+    from tests.harness import Case
+    kw = dict(B=1, Hq=1, Hkv=1, dtype=synth.FP16, bits=2, g=32, n_rows=2)
+    period = None
+    if case == "ties_top_class":
+        S, k, period = 70000, 500, 32
+    elif case == "ties_second_class":
+        S, k, period = 200000, 4000, 64
+    elif case == "all_equal":
+        S, k, period = 70000, 500, 1
+    elif case == "crowded":
+        S, k = 40000, 600
+    elif case == "gqa":
+        S, k = 40000, 300
+        kw.update(Hq=4, Hkv=1, dtype=synth.BF16, bits=1)
+    else:
+        S, k = 4096, 64
+    c = Case(kw["B"], kw["Hq"], kw["Hkv"], S, kw["dtype"], kw["bits"], kw["g"], k, seed=560 + len(case), n_rows=2)
+    if period:
+        c.k_bits = np.ascontiguousarray(c.k_bits[:, :, np.arange(S) % period])
+    if case == "crowded":
+        u = np.where(np.random.default_rng(7).random(128) < 0.5, -8.0, 8.0).astype(np.float32)
+        hot = np.stack([u if i % 2 == 0 else -u for i in range(1200)])
+        c.k_bits[0, 0, 1024:1024 + 1200] = synth.to_bits(hot, kw["dtype"]).reshape(1200, 128)
+    try:
+        c.load()
+        for t in range(2):
+            c.append_token(t)
+            c.decode_step(check_logits=False)
+        if period:
+            assert c.stats["band_diffs"] == 0, c.stats
+        print(case, c.stats)
+    finally:
+        c.close()
+
+
 @pytest.mark.parametrize("Hq,Hkv,dtype,bits,g", [(8, 2, synth.BF16, 2, 64), (8, 2, synth.FP16, 1, 32), (8, 1, synth.BF16, 2, 32)])
 def test_matrix_core_value_path_keeps_fp32_accuracy(Hq, Hkv, dtype, bits, g):
     """With 8 or 16 query rows per KV head the value side of attend runs on the matrix cores with f16 operands
