@@ -107,6 +107,7 @@ class Run:
         layers = args.layers or layers
         k = args.topk or k
         g = args.group or g
+        bits = args.bits or bits
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k = B, Hq, Hkv, S, dtype, bits, g, k
         self.G, self.D, self.R = Hq // Hkv, 128, max(64, g)
         self.total_steps = total_steps
@@ -383,6 +384,8 @@ def main():
                     help="override k, the number of prefetched pairs per (batch, KV head) (the k sweep of Section 4.4)")
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="override g, the quantisation group size (the residual becomes max(64, g))")
+    ap.add_argument("--bits", type=int, default=0, choices=[0, 1, 2, 4],
+                    help="override the code width (4: Eq. 2 with B = 4, plain kernels; the paper's runs use 2 and 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-gather", action="store_true", help="skip the host-link gather (attend sees nothing prefetched)")
     ap.add_argument("--serial-gather", action="store_true", help="issue the gather on the main stream (no overlap)")
@@ -439,6 +442,7 @@ def main():
     layers = args.layers or layers
     k = args.topk or k
     g = args.group or g
+    bits = args.bits or bits
     G, D = Hq // Hkv, 128
     spec = args.variant == "speculative"
     one_pass_kernel = G == 1 and bits == 2 and spec and args.select_cache == "lowbit" and not args.vector_alu
@@ -488,9 +492,11 @@ def main():
     pairs = rows * ((k if not args.no_gather else 0) + (N - Nq) + 1) * 512   # staged, residual and transient 16-bit pairs
     us_layer = ms_per_step * 1e3 / layers
     n_q_rows = G * (2 if spec else 1)
-    score_name = ("score_i8_kernel" if (G == 1 and spec and args.vector_alu not in ("score", "both"))
+    score_name = ("score4_kernel" if bits == 4 else
+                  "score_i8_kernel" if (G == 1 and spec and args.vector_alu not in ("score", "both"))
                   else "score_mfma_kernel" if n_q_rows % 8 == 0 else "score_kernel")
-    attend_name = "attend_i8_kernel" if (G == 1 and spec and bits == 2 and args.vector_alu not in ("attend", "both")) else "attend_partial_kernel"
+    attend_name = ("attend4_partial_kernel" if bits == 4 else
+                   "attend_i8_kernel" if (G == 1 and spec and bits == 2 and args.vector_alu not in ("attend", "both")) else "attend_partial_kernel")
     one_pass_name = "attend_i8_kernel<scoring pass in front>"
     stream_peak = peaks["hbm_stream_peak_gbs"]
     link_peak = peaks["link_peak_gbs"]
@@ -567,7 +573,7 @@ def main():
         "dtype_note": "accumulation and outputs are binary32; the contractions run on the matrix cores with int8 operands (packed "
                       "codes, fixed-point multipliers, exact int32 sums) or, with 8 and 16 query rows per KV head, f16 operands",
         "data": "synthetic" if not args.filler_mb else f"synthetic; EMULATED rest of the layer: {args.filler_mb} MB streamed per layer",
-        "config": {"workload": DESCR[args.workload], "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
+        "config": {"workload": DESCR[args.workload] + (f" [code width overridden: {bits} bits]" if args.bits else ""), "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
                    "residual": run.R, "group": g, "topk": k, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend, the gather of "
                                    "the next step's pairs on side streams",

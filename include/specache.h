@@ -65,7 +65,7 @@ typedef struct specache_config {
                            two query rows of a decode step: up to 16 rows per KV head) */
     int32_t n_kv_heads; /* Hkv >= 1                                                    */
     int32_t head_dim;   /* must be 128                                                 */
-    int32_t bits;       /* 1 (Eq. 3) or 2 (Eq. 2)                                      */
+    int32_t bits;       /* 1 (Eq. 3), 2 (Eq. 2; the paper's two widths) or 4 (Eq. 2)    */
     int32_t group;      /* g: 32, 64 (the paper's) or 128; keys grouped per channel over
                            g tokens, values per token over g channels                  */
     int32_t residual;   /* R: multiple of g, g <= R <= 256.  Tokens are appended one at

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecache.so")
 STAMP = os.path.join(HERE, "libspecache.srchash")   # hash of the sources the library was built from
-SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "select.hip", "topk.hip", "gather.hip", "attend.hip", "attend_i8.hip", "measure.hip"]
+SOURCES = ["specache.hip", "quant.hip", "score.hip", "score_mfma.hip", "score_i8.hip", "select.hip", "topk.hip", "gather.hip", "attend.hip", "attend_i8.hip", "fourbit.hip", "measure.hip"]
 # -ffp-contract=off: the quantiser's binary32 operation order is part of its definition and
 # fused multiply-adds are written out where they are wanted.  Packed FP32 code generation is
 # switched off for the device pass.

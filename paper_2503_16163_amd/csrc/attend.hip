@@ -635,6 +635,23 @@ hipError_t launch_attend(const LayerView& L, const void* q, int n_rows, int N, i
     A.Nq = Nq;
     A.sm_scale = sm_scale;
     const int n_ex = (slot_idx ? L.topk : 0) + (N - Nq) + (k_spec ? 1 : 0);
+    if (L.bits == 4) {
+        // 4-bit codes: a plain partial pass of their own, the merge kernel of the other widths
+        const int NR = L.G * n_rows;
+        if (phases & kAttendPartial) {
+            const AttendArgs4 a4{q, logits, logit_stride, slot, slot_idx, k_spec, v_spec, scratch.part_o, scratch.part_ml,
+                                 scratch.max_chunks, N, Nq, sm_scale};
+            hipError_t e = launch_attend4_partial(L, a4, n_rows, stream);
+            if (e != hipSuccess) return e;
+        }
+        if (phases & kAttendCombine) {
+            const int n_chunks = attend_chunks(NR, Nq, n_ex);
+            if (n_chunks > kCombineMaxChunks || n_chunks > scratch.max_chunks) return hipErrorInvalidValue;
+            SPC_LAUNCH(attend_combine_kernel, dim3(L.rows * NR), dim3(kCombineThreads), stream, scratch.part_o, scratch.part_ml,
+                       scratch.max_chunks, n_chunks, NR, out);
+        }
+        return hipGetLastError();
+    }
     // one query head per KV head, two rows, 2-bit values: the partial pass with the value side on the
     // integer matrix cores (same chunking, same partial-result format, same merge kernel)
     if ((phases & kAttendPartial) && attend_uses_int8_matrix_cores(L, n_rows) && !(kernel_choice() & kChoiceAttendValu)) {

@@ -130,6 +130,29 @@ hipError_t launch_attend_i8_partial(const LayerView& L, const void* q, int N, in
 enum { kChoiceScoreValu = 1, kChoiceAttendValu = 2, kChoiceKeepLogits = 4 };
 int& kernel_choice();
 
+// 4-bit codes: plain kernels on a layout of their own (fourbit.hip); the merge kernel, the gather, ArgTopK and
+// the append are shared with the other widths
+struct AttendArgs4 {
+    const void* q;
+    const float* logits;
+    size_t logit_stride;
+    const uint16_t* slot;
+    const int32_t* slot_idx;
+    const void* k_spec;
+    const void* v_spec;
+    float* part_o;
+    float* part_ml;
+    int max_chunks, N, Nq;
+    float sm_scale;
+};
+hipError_t launch_flush4(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0, int Nq0, int n_flush,
+                         hipStream_t stream);
+hipError_t launch_export4(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz, uint8_t* v_codes,
+                          uint16_t* v_mnmx, float* v_sz, hipStream_t stream);
+hipError_t launch_score4(const LayerView& L, const void* q, int n_rows, int Nq, float sm_scale, float* logits, size_t logit_stride,
+                         uint32_t* keys, size_t key_stride, hipStream_t stream);
+hipError_t launch_attend4_partial(const LayerView& L, const AttendArgs4& a, int n_rows, hipStream_t stream);
+
 // export: canonical unpacked view of rows' quantised prefix into device buffers
 hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz,
                          uint8_t* v_codes, uint16_t* v_mnmx, float* v_sz, hipStream_t stream);

@@ -348,6 +348,7 @@ hipError_t export_dispatch(const LayerView& L, int Nq, uint8_t* k_codes, uint16_
 hipError_t launch_flush(const LayerView& L, const void* k_new, const void* v_new, int n_new, int N0, int Nq0,
                         int n_flush, hipStream_t stream) {
     if (n_flush <= 0) return hipSuccess;
+    if (L.bits == 4) return launch_flush4(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 2 && L.group == 32) return flush_dispatch<2, 32>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 2 && L.group == 64) return flush_dispatch<2, 64>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
     if (L.bits == 1 && L.group == 32) return flush_dispatch<1, 32>(L, k_new, v_new, n_new, N0, Nq0, n_flush, stream);
@@ -369,6 +370,7 @@ hipError_t launch_append_copy(const LayerView& L, const void* k_new, const void*
 hipError_t launch_export(const LayerView& L, int Nq, uint8_t* k_codes, uint16_t* k_mnmx, float* k_sz,
                          uint8_t* v_codes, uint16_t* v_mnmx, float* v_sz, hipStream_t stream) {
     if (Nq <= 0) return hipSuccess;
+    if (L.bits == 4) return launch_export4(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 2 && L.group == 32) return export_dispatch<2, 32>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 2 && L.group == 64) return export_dispatch<2, 64>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);
     if (L.bits == 1 && L.group == 32) return export_dispatch<1, 32>(L, Nq, k_codes, k_mnmx, k_sz, v_codes, v_mnmx, v_sz, stream);

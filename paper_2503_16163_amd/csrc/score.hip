@@ -285,6 +285,7 @@ hipError_t launch_score(const LayerView& L, const void* q, int n_rows, int Nq, f
                         size_t logit_stride, uint32_t* keys, size_t key_stride, hipStream_t stream) {
     if (Nq <= 0) return hipSuccess;
     if (L.group != 32 && L.group != 64 && L.group != 128) return hipErrorInvalidValue;
+    if (L.bits == 4) return launch_score4(L, q, n_rows, Nq, sm_scale, logits, logit_stride, keys, key_stride, stream);
     // two rows of one query head: the integer matrix cores take the contraction (it reads q 16 bytes at a
     // time; the C ABI rejects a q that is not 16-byte aligned)
     if (score_uses_int8_matrix_cores(L.G, n_rows) && !(kernel_choice() & kChoiceScoreValu))

@@ -322,7 +322,7 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
     const int G = c.n_q_heads / c.n_kv_heads;
     if (G != 1 && G != 2 && G != 4 && G != 8) return fail(nullptr, SPECACHE_EINVAL, "n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
     if (c.head_dim != kD) return fail(nullptr, SPECACHE_EINVAL, "head_dim must be 128");
-    if (c.bits != 1 && c.bits != 2) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1 or 2");
+    if (c.bits != 1 && c.bits != 2 && c.bits != 4) return fail(nullptr, SPECACHE_EINVAL, "bits must be 1, 2 or 4");
     if (c.one_bit_form != SPECACHE_1BIT_IMPROVED && c.one_bit_form != SPECACHE_1BIT_KIVI)
         return fail(nullptr, SPECACHE_EINVAL, "one_bit_form must be SPECACHE_1BIT_IMPROVED or SPECACHE_1BIT_KIVI");
     if (c.async_select < 0 || c.async_select > 2) return fail(nullptr, SPECACHE_EINVAL, "async_select must be 0, 1 or 2");
@@ -612,7 +612,8 @@ int specache_append_score(specache_ctx* ctx, int32_t layer, const void* k_new, c
     if (specache_plan_append(ctx->cfg.residual, ctx->cfg.group, L.N, L.Nq, 1, &n_flush) != SPECACHE_OK)
         return fail(ctx, SPECACHE_ESTATE, "inconsistent token counts");
     // a group leaves the residual with this token, or nothing is quantised yet (no scoring launch): two steps
-    if (n_flush > 0 || L.Nq == 0) {
+    // (the 4-bit scoring kernel carries no append)
+    if (n_flush > 0 || L.Nq == 0 || ctx->cfg.bits == 4) {
         if (int rc = specache_quantize_append(ctx, layer, k_new, v_new, 1, stream)) return rc;
         return score_impl(ctx, layer, q, n_rows, stream, nullptr, nullptr);
     }

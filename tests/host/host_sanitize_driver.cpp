@@ -50,6 +50,7 @@ int main() {
         return rc == SPECACHE_EINVAL && ctx == nullptr && std::strlen(specache_last_error(nullptr)) > 0;
     };
     { specache_config c = base; c.bits = 3; REQUIRE(rejected(c)); }
+    { specache_config c = base; c.bits = 8; REQUIRE(rejected(c)); }
     { specache_config c = base; c.group = 48; REQUIRE(rejected(c)); }
     { specache_config c = base; c.residual = 48; REQUIRE(rejected(c)); }
     { specache_config c = base; c.residual = 512; REQUIRE(rejected(c)); }

@@ -48,6 +48,11 @@ def test_config1_single_head():
     (1, 8, 2, 1500, synth.BF16, 1, 128, 50, 256),    # 1-bit g128, GQA 4:1, R = 256
     (2, 4, 2, 1000, synth.FP16, 2, 128, 32, 128),    # g128, GQA 2:1
     (1, 8, 1, 900, synth.BF16, 2, 128, 40, 256),     # g128, GQA 8:1
+    (2, 3, 3, 1500, synth.FP16, 4, 32, 128, 64),     # 4-bit codes (Eq. 2, B = 4): MHA, ragged tail
+    (1, 8, 2, 2112, synth.BF16, 4, 64, 96, 64),      # 4-bit, GQA 4:1, g = R = 64
+    (1, 8, 1, 900, synth.BF16, 4, 128, 40, 256),     # 4-bit, g128, GQA 8:1 (16 query rows per KV head)
+    (1, 4, 2, 1300, synth.FP16, 4, 32, 64, 96),      # 4-bit, GQA 2:1, R = 96
+    (1, 2, 1, 700, synth.FP16, 4, 128, 32, 128),     # 4-bit, g128, GQA 2:1
 ])
 def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
     from tests.harness import Case
@@ -56,7 +61,8 @@ def test_small_configs(B, Hq, Hkv, S, dtype, bits, g, k, R):
 
 
 @pytest.mark.parametrize("dtype,bits,g", [(synth.FP16, 2, 32), (synth.BF16, 2, 64), (synth.FP16, 1, 32), (synth.BF16, 1, 64),
-                                          (synth.FP16, 2, 128), (synth.BF16, 1, 128)])
+                                          (synth.FP16, 2, 128), (synth.BF16, 1, 128),
+                                          (synth.FP16, 4, 32), (synth.BF16, 4, 64), (synth.FP16, 4, 128)])
 def test_quantiser_on_rounding_boundaries(dtype, bits, g):
     """Inputs on a grid of half quantisation steps (and their 16-bit neighbours), constant groups and groups
     with tiny ranges: the quotients of Eq. 2 / Eq. 3 land exactly on, or one rounding away from, the
@@ -66,7 +72,7 @@ def test_quantiser_on_rounding_boundaries(dtype, bits, g):
     rng = np.random.default_rng(77)
     shape = c.k_bits.shape
     for name in ("k_bits", "v_bits"):
-        m = rng.integers(0, 7 if bits == 2 else 5, size=shape)              # half steps of a unit-scale group
+        m = rng.integers(0, {1: 5, 2: 7, 4: 31}[bits], size=shape)          # half steps of a unit-scale group
         e = rng.integers(-6, 5, size=(shape[0], shape[1], shape[2] // g, 1)).repeat(g, axis=2)
         if name == "v_bits":
             e = rng.integers(-6, 5, size=(shape[0], shape[1], shape[2], shape[3] // g)).repeat(g, axis=3)
@@ -192,7 +198,7 @@ def test_integer_matrix_core_scoring_keeps_fp32_accuracy(dtype, bits, g, spread)
         c.close()
 
 
-@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128), (2, 128, 128)])
+@pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128), (2, 128, 128), (4, 32, 64), (4, 128, 256)])
 def test_long_decode_crosses_flushes(bits, g, R):
     """70 decode steps from a short prompt: the residual ring wraps and groups are flushed during decoding
     (every g steps), each step checked against the oracle, the whole quantised prefix and the offloaded rows
@@ -730,7 +736,7 @@ def test_error_paths():
         assert ei.value.code == binding.ESTATE
     finally:
         sc.close()
-    for kwargs in [dict(bits=3), dict(group=48), dict(residual=48), dict(max_seq=100), dict(topk=0), dict(head_dim=64),
+    for kwargs in [dict(bits=3), dict(bits=8), dict(group=48), dict(residual=48), dict(max_seq=100), dict(topk=0), dict(head_dim=64),
                    dict(n_q_heads=3, n_kv_heads=2)]:
         base = dict(n_layers=1, batch=1, n_q_heads=2, n_kv_heads=2, bits=2, group=32, max_seq=256, topk=16,
                     dtype=synth.FP16)

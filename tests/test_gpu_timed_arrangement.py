@@ -30,6 +30,8 @@ SHAPES = {
     "config3": (16, 32, 32, 2048, synth.FP16, 2, 32, 128, 4),
     "config4": (4, 32, 8, 32768, synth.BF16, 2, 64, 512, 4),
     "config5": (1, 32, 8, 131072, synth.BF16, 1, 32, 1024, 4),
+    "M0_4bit": (1, 32, 32, 32768, synth.FP16, 4, 32, 256, 4),       # the 7B shape with 4-bit codes (Eq. 2, B = 4)
+    "config4_4bit_g128": (4, 32, 8, 32768, synth.BF16, 4, 128, 512, 2),
 }
 STEPS = 8
 
