@@ -125,6 +125,8 @@ class Run:
         else:
             async_select = {"main": 0, "own": 1, "gather": 2 if side_gathers else 1}[args.select_stream]
         self.async_select = async_select
+        self.carry_append = calls == "one-pass" and (args.append == "carried" or
+                                                     (args.append == "auto" and arrangement.carry_append(self.G, S, k)))
         max_seq = ((S + total_steps + 63) // 64 + 1) * 64
         sc = None
         while sc is None:
@@ -204,7 +206,7 @@ class Run:
         if not self.spec:
             return "quantize_append, score_topk, gather (main stream), attend"
         if self.calls == "one-pass":
-            return "quantize_append, score_attend, select_gather"
+            return "append_score_attend, select_gather" if self.carry_append else "quantize_append, score_attend, select_gather"
         if self.async_select == 2:
             return "append_score, select_gather, attend" if self.args.fused_append else "quantize_append, score, select_gather, attend"
         return "quantize_append, score_topk, gather, attend"
@@ -230,8 +232,11 @@ class Run:
             q = self.q_p[t % self.nq_pool][L]
             ib = self.idx_p[L][t % 2]
             if self.calls == "one-pass":
-                sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
-                sc.score_attend(L, q, 2, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h)
+                if not self.carry_append:
+                    sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
+                    sc.score_attend(L, q, 2, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h)
+                else:   # the one launch also carries the append of the new pair
+                    sc.append_score_attend(L, k_p[t], v_p[t], q, 2, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h)
                 sc.select_gather(L, ib, (t + 1) % 2 if do_gather else -1, side_h[L % n_side])
             else:
                 if self.async_select == 2:
@@ -416,6 +421,10 @@ def main():
     ap.add_argument("--fused-append", action="store_true",
                     help="with --calls split and ArgTopK on the gather's stream: specache_append_score (the scoring launch "
                          "carries the copy of the new pair) instead of quantize_append and score as two calls")
+    ap.add_argument("--append", default="auto", choices=["auto", "carried", "separate"],
+                    help="with --calls one-pass: specache_append_score_attend, whose one launch also carries the copy of "
+                         "the new pair (carried), or quantize_append and specache_score_attend as two calls (separate); "
+                         "auto = the measured rule of paper_2503_16163_amd.arrangement")
     ap.add_argument("--vector-alu", default="", choices=["", "score", "attend", "both"],
                     help="A/B measurement: run the named streaming kernel(s) in the vector-ALU formulation instead of the "
                          "integer-matrix-core one (one query head per KV head, two rows); implies --calls split")

@@ -258,6 +258,20 @@ int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32
                           const void* v_spec, int32_t slot, float* out, void* stream);
 
 /*
+ * specache_quantize_append of ONE token followed by specache_score_attend, as one call: a whole layer-step on
+ * the caller's stream but for the selection and the prefetch (Appendix A "Decoding": C' = [C', Quant(K_t, V_t)],
+ * C = [C, Offload(C_t)], A, O).  k_new, v_new: device, 16-bit, [B, Hkv, 1, 128].  Where specache_score_attend
+ * runs as one launch and the token does not complete a group that leaves the residual, that launch also
+ * carries the Offload of the new pair to the CPU copy and to the residual (the attention reads the pair from
+ * k_new / v_new, which must stay unchanged until the launch has run): one launch less per layer-step.
+ * Otherwise the steps run one after the other.  Results are those of the separate calls.
+ * Errors: those of the separate calls.
+ */
+int specache_append_score_attend(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                                 int32_t n_rows, const void* k_spec, const void* v_spec, int32_t slot, float* out,
+                                 void* stream);
+
+/*
  * specache_attend for callers that must not allocate device memory around the call and want
  * the call's scratch out of the context: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the partial

@@ -9,7 +9,13 @@ needs the fewest ordering calls between streams; three side streams below 192 ke
 selects while two gathers share the link), two from there on.  With little of it the step is bound by
 the host link: ArgTopK on the library's own stream lets every gather start the moment its selection is
 done; two side streams, or one from 384 keys per pair on, where the gather has time to spare.  One
-layer, or the non-speculative variant: everything on the caller's stream."""
+layer, or the non-speculative variant: everything on the caller's stream.
+
+Whether the launch that scores (and attends) also carries the append of the step's new pair
+(specache_append_score, specache_append_score_attend) follows the same measure: from 192 keys per pair
+on it saves a launch per layer-step (7B shape, k = 64: 38 to 40 us per layer against 43 to 46; k = 128: 43
+against 51); below, where the link is the bound, the separate append measured faster (k = 256: 76.6 us
+against 80 to 85 with the append carried, whichever number of side streams)."""
 
 SELECT_ON_CALLER, SELECT_ON_OWN_STREAM, SELECT_ON_GATHER_STREAM = 0, 1, 2
 
@@ -19,6 +25,10 @@ def side_streams(async_select, G, S, k):
     if async_select == SELECT_ON_GATHER_STREAM:
         return 3 if keys_per_pair < 192 else 2
     return 1 if keys_per_pair >= 384 else 2
+
+
+def carry_append(G, S, k):
+    return G * S / k >= 192
 
 
 def pick(G, S, k, layers, speculative=True, side_gathers=True):

@@ -158,18 +158,21 @@ __device__ __forceinline__ void attend_extra_chunk(const LayerView& L, const Att
     if (tid < n) {
         const int x = x0 + tid;
         const uint16_t* kp = nullptr;
-        bool spec = false;
+        bool spec = false, fresh = false;
         if (x < ks) {
             const int t = t_staged;
             if (t >= 0 && t < A.Nq) kp = A.slot + ((size_t)row * L.topk + x) * 256;
         } else if (x < ks + n_res) {
             const int t = A.Nq + (x - ks);
             kp = L.ring + ((size_t)row * L.R + (t % L.R)) * 256;
+            // a token that this very launch appends (its copy into the ring may not have landed yet) is read
+            // from the caller's buffers
+            fresh = L.tail_k != nullptr && t == L.tail_N0;
         } else {
             spec = true;
         }
-        src_k[tid] = spec ? A.k_spec + (size_t)row * kD : kp;
-        src_v[tid] = spec ? A.v_spec + (size_t)row * kD : (kp ? kp + kD : nullptr);
+        src_k[tid] = spec ? A.k_spec + (size_t)row * kD : fresh ? L.tail_k + (size_t)row * kD : kp;
+        src_v[tid] = spec ? A.v_spec + (size_t)row * kD : fresh ? L.tail_v + (size_t)row * kD : (kp ? kp + kD : nullptr);
         src_spec[tid] = spec;
     }
     __syncthreads();

@@ -360,13 +360,13 @@ __device__ __forceinline__ void merge_waves(const uint8_t* areas, int area_strid
 }
 
 // (row, chunk) of this workgroup: the 16-bit chunks are chains of dependent loads and are dispatched first
-__device__ __forceinline__ void chunk_of_block(const AttendArgs& A, int rows, int& row, int& chunk) {
+__device__ __forceinline__ void chunk_of_block(const AttendArgs& A, int rows, int bid, int& row, int& chunk) {
     const int n_extra = A.n_chunks - A.n_main;
-    if ((int)blockIdx.x < rows * n_extra) {
-        row = blockIdx.x / n_extra;
-        chunk = A.n_main + blockIdx.x % n_extra;
+    if (bid < rows * n_extra) {
+        row = bid / n_extra;
+        chunk = A.n_main + bid % n_extra;
     } else {
-        const int id = blockIdx.x - rows * n_extra;
+        const int id = bid - rows * n_extra;
         row = id / A.n_main;
         chunk = id % A.n_main;
     }
@@ -399,8 +399,22 @@ __global__ __launch_bounds__(kThreads) void attend_i8_kernel(LayerView L, Attend
     __shared__ WaveOut wout;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int n_tail = L.tail_k ? L.rows : 0;
+    if ((int)blockIdx.x < n_tail) {
+        // a launch that also appends the step's new token (Appendix A "Decoding": Offload of the new pair to the
+        // CPU copy; it also joins the 16-bit residual): one more workgroup per row, 32 lanes x 16 bytes.  They are
+        // dispatched first: the store to host memory crosses a link the prefetch keeps busy, and the launch
+        // ends only when it has landed.
+        const int r = blockIdx.x;
+        if (tid < 32) {
+            const uint4 v = reinterpret_cast<const uint4*>(tid < 16 ? L.tail_k : L.tail_v)[(size_t)r * 16 + (tid & 15)];
+            reinterpret_cast<uint4*>(L.host)[((size_t)r * L.max_seq + L.tail_N0) * 32 + tid] = v;
+            reinterpret_cast<uint4*>(L.ring)[((size_t)r * L.R + (L.tail_N0 % L.R)) * 32 + tid] = v;
+        }
+        return;
+    }
     int row, chunk;
-    chunk_of_block(A, L.rows, row, chunk);
+    chunk_of_block(A, L.rows, (int)blockIdx.x - n_tail, row, chunk);
     float* po = A.part_o + (((size_t)row * A.max_chunks + chunk) * NR) * kD;
     float* pml = A.part_ml + (((size_t)row * A.max_chunks + chunk) * NR) * 2;
 
@@ -498,7 +512,7 @@ hipError_t launch_attend_i8_partial(const LayerView& L, const void* q, int N, in
     A.n_main = (Nq + kI8Chunk - 1) / kI8Chunk;
     A.n_chunks = A.n_main + (n_ex + kExtraChunk - 1) / kExtraChunk;
     if (A.n_chunks > A.max_chunks || A.n_chunks < 1) return hipErrorInvalidValue;
-    const dim3 grid(A.n_chunks * L.rows), block(kThreads);
+    const dim3 grid(A.n_chunks * L.rows + (L.tail_k ? L.rows : 0)), block(kThreads);
 #define SPC_AI8(G_, F_)                                                                                                \
     do {                                                                                                               \
         if (keys) SPC_LAUNCH((attend_i8_kernel<G_, F_, true>), grid, block, stream, L, A, sm_scale, keys, key_stride); \

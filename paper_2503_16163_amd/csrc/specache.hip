@@ -743,15 +743,27 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
     return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, nullptr);
 }
 
-int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
-                          const void* v_spec, int32_t slot, float* out, void* stream) {
+// specache_score_attend, optionally with the append of one new token in front (carried by the same launch when
+// that launch exists and no group leaves the residual with the token)
+static int score_attend_impl(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                             int32_t n_rows, const void* k_spec, const void* v_spec, int32_t slot, float* out, void* stream) {
     if (int rc = check_ctx_layer(ctx, layer)) return rc;
     if (!ctx->select_on_gather)
         return fail(ctx, SPECACHE_ESTATE, "specache_score_attend needs async_select = SPECACHE_SELECT_STREAM_GATHER");
+    if ((k_new == nullptr) != (v_new == nullptr)) return fail(ctx, SPECACHE_EINVAL, "k_new and v_new must both be given or both be null");
     Layer& L = ctx->layers[layer];
+    int32_t n_flush = 0;
+    if (k_new) {
+        if ((long)L.N + 1 > ctx->cfg.max_seq) return fail(ctx, SPECACHE_ECAPACITY, "append exceeds max_seq");
+        if (specache_plan_append(ctx->cfg.residual, ctx->cfg.group, L.N, L.Nq, 1, &n_flush) != SPECACHE_OK)
+            return fail(ctx, SPECACHE_ESTATE, "inconsistent token counts");
+    }
     const bool one_pass = L.view.G == 1 && n_rows == 2 && attend_uses_int8_matrix_cores(L.view, n_rows) && L.Nq > 0 &&
                           ctx->cfg.select_cache == SPECACHE_SELECT_LOWBIT && q && out && !((uintptr_t)q & 15) &&
                           !(kernel_choice() & (kChoiceScoreValu | kChoiceAttendValu));
+    const bool carry = k_new && one_pass && n_flush == 0;
+    if (k_new && !carry)
+        if (int rc = specache_quantize_append(ctx, layer, k_new, v_new, 1, stream)) return rc;
     if (!one_pass) {
         // other shapes and options: the two passes one after the other, same results
         if (int rc = score_impl(ctx, layer, q, n_rows, stream, nullptr, nullptr)) return rc;
@@ -765,12 +777,20 @@ int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32
     if (slot >= 0 && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
     const bool keep = (kernel_choice() & kChoiceKeepLogits) != 0;
+    LayerView view = L.view;
+    if (carry) {
+        view.tail_k = (const uint16_t*)k_new;
+        view.tail_v = (const uint16_t*)v_new;
+        view.tail_N0 = L.N;
+    }
+    const int N1 = L.N + (carry ? 1 : 0);
     {
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE_ATTEND, /*kernel_events=*/true);
-        SPC_HIP(ctx, launch_attend_i8_partial(L.view, q, L.N, L.Nq, ctx->sm_scale, nullptr, ctx->logit_stride,
+        SPC_HIP(ctx, launch_attend_i8_partial(view, q, N1, L.Nq, ctx->sm_scale, nullptr, ctx->logit_stride,
                                               slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
                                               v_spec, ctx->scratch, L.keys, ctx->logit_stride, keep ? ctx->logits : nullptr, st));
     }
+    L.N = N1;   // only once the launch that copies the token is enqueued
     ctx->logits_kept = keep;
     // the keys are complete here: the selection on the side stream can start while the chunks are merged
     if (int rc = record_scored(ctx, L, layer, n_rows, st)) return rc;
@@ -781,6 +801,18 @@ int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32
                                    ctx->scratch, out, kAttendCombine, st));
     }
     return record_attended(ctx, L, slot, st);
+}
+
+int specache_score_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
+                          const void* v_spec, int32_t slot, float* out, void* stream) {
+    return score_attend_impl(ctx, layer, nullptr, nullptr, q, n_rows, k_spec, v_spec, slot, out, stream);
+}
+
+int specache_append_score_attend(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                                 int32_t n_rows, const void* k_spec, const void* v_spec, int32_t slot, float* out,
+                                 void* stream) {
+    if (ctx && (!k_new || !v_new)) return fail(ctx, SPECACHE_EINVAL, "null k_new or v_new");
+    return score_attend_impl(ctx, layer, k_new, v_new, q, n_rows, k_spec, v_spec, slot, out, stream);
 }
 
 int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,

@@ -72,7 +72,7 @@ class Case:
         cap = max_seq or ((S + 64 + 63) // 64) * 64
         self.one_bit_form, self.select_form, self.select_cache = one_bit_form, select_form, select_cache
         self.async_select = async_select
-        self.fused_append = bool(fused_append) and async_select == 2   # specache_append_score in decode_step
+        self.fused_append = bool(fused_append) and async_select == 2   # specache_append_score[_attend] in decode_step
         self.one_pass = bool(one_pass) and async_select == 2           # specache_score_attend in decode_step
         self.pending = None
         self.staged_idx = None       # index lists of the last gather (what a mixed-cache selection scores in 16 bits)
@@ -169,8 +169,11 @@ class Case:
         out = torch.empty((self.B, self.Hq, nr, self.D), dtype=torch.float32, device="cuda")
         slot = (t % 2) if (t > 0 and do_gather) else -1
         if self.one_pass:            # scoring and attention in one call, then the selection and the gather
-            self._flush_pending()
-            self.sc.score_attend(0, q, nr, ks, vs, slot, out, main)
+            if self.pending is not None:
+                self.sc.append_score_attend(0, self.pending[0], self.pending[1], q, nr, ks, vs, slot, out, main)
+                self.pending = None
+            else:
+                self.sc.score_attend(0, q, nr, ks, vs, slot, out, main)
             self.sc.select_gather(0, idx, (t + 1) % 2 if do_gather else -1, self.side)
         elif self.async_select == 2:   # ArgTopK on the gather's stream: the other pair of calls
             if self.pending is not None:

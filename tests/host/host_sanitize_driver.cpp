@@ -80,6 +80,8 @@ int main() {
     REQUIRE(specache_select_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_attend(nullptr, 0, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);
+    REQUIRE(specache_score_attend(nullptr, 0, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);
+    REQUIRE(specache_append_score_attend(nullptr, 0, nullptr, nullptr, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_attend_static(nullptr, 0, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_debug_poison_slot(nullptr, 0, 0, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_export_quantized(nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == SPECACHE_EINVAL);

@@ -509,13 +509,17 @@ def test_append_carried_by_the_scoring_launch(Hq, Hkv, dtype, bits, g, R):
     (4, 2, 1500, synth.FP16, 2, 32, 64, 32),        # two query heads per KV head: the two calls one after the other
     (2, 2, 1500, synth.BF16, 1, 32, 64, 32),        # 1-bit codes: likewise
 ])
-def test_scoring_and_attention_in_one_pass(Hq, Hkv, S, dtype, bits, g, R, k):
+@pytest.mark.parametrize("carry_append", [False, True])
+def test_scoring_and_attention_in_one_pass(Hq, Hkv, S, dtype, bits, g, R, k, carry_append):
     """specache_score_attend: one launch scores a chunk's packed keys, keeps the logits on the chip and reads the
     chunk's packed values (one query head per KV head, two rows, 2-bit codes); other shapes run the two calls.
-    40 decode steps across flushes; every step's selection, logits (kept on request) and output against the oracle."""
+    40 decode steps across flushes; every step's selection, logits (kept on request) and output against the oracle.
+    carry_append: specache_append_score_attend, the same launch also appends the step's new token (on the steps
+    that flush nothing); the offloaded rows are compared at the end."""
     from tests.harness import Case
     binding.debug_kernel_choice(binding.KEEP_ONE_PASS_LOGITS)
-    c = Case(1, Hq, Hkv, S, dtype, bits, g, k, R=R, seed=3600 + Hq + g + bits, async_select=2, one_pass=True)
+    c = Case(1, Hq, Hkv, S, dtype, bits, g, k, R=R, seed=3600 + Hq + g + bits, async_select=2, one_pass=True,
+             fused_append=carry_append)
     try:
         c.load()
         c.decode_step()                      # nothing staged yet (slot -1)
@@ -523,6 +527,8 @@ def test_scoring_and_attention_in_one_pass(Hq, Hkv, S, dtype, bits, g, R, k):
             c.append_token(t)
             c.decode_step(check_logits=(t % 8 == 0))
         c.check_quantized()
+        c.check_offload(first=c.S, count=40)
+        assert c.sc.counts(0)[0] == S + 40
         print(c.stats)
     finally:
         c.close()

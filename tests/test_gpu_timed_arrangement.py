@@ -110,7 +110,10 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
             slot = (t % 2) if t > 0 else -1
             for L in range(layers):
                 side = sides[L % n_side]
-                if one_pass:
+                if one_pass and fused_append:
+                    sc.append_score_attend(L, nkd, nvd, q, 2, ks, vs, slot, out[L][t], main)
+                    sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, side)
+                elif one_pass:
                     sc.quantize_append(L, nkd, nvd, 1, main)
                     sc.score_attend(L, q, 2, ks, vs, slot, out[L][t], main)
                     sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, side)
@@ -175,8 +178,16 @@ def test_full_size_all_rows_in_the_timed_arrangement(name):
 
 @pytest.mark.timeout(600)
 def test_full_size_fused_append_in_the_timed_arrangement():
-    """bench.py --fused-append at the headline shape: the scoring launch carries the append."""
+    """bench.py --calls split --fused-append at the headline shape: the scoring launch carries the append."""
     run_free_running("M0_7B_32k", fused_append=True)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["M0_7B_32k", "config3"])
+def test_full_size_whole_layer_step_in_one_call(name):
+    """specache_append_score_attend: append, scoring and attention of a layer-step in one call (one launch where
+    no group leaves the residual), then select_gather: what bench.py times by default at these shapes."""
+    run_free_running(name, one_pass=True, fused_append=True)
 
 
 @pytest.mark.timeout(900)
@@ -204,6 +215,8 @@ def test_poisoned_staging_slots_show_no_read_before_gather(async_select, n_side)
     if async_select == 2:
         shape = (2, 4, 4, 2300, synth.FP16, 2, 32, 72, 3)
         run_free_running("poison-one-pass", poison=True, steps=12, shape=shape, arrange=(async_select, n_side), one_pass=True)
+        run_free_running("poison-one-call", poison=True, steps=40, shape=shape, arrange=(async_select, n_side), one_pass=True,
+                         fused_append=True)
 
 
 def test_misaligned_query_is_an_error():
