@@ -345,25 +345,34 @@ def check_last_step_and_time_oracle(run, time_budget_s=25.0):
                              "ArgTopK by the tie-band rule, attention output with the staged pairs to 2e-3"}
 
 
-def profile_figures(workload, kernel_names):
-    """HBM traffic and vector-instruction counts per launch from the committed rocprofv3 --pmc summaries, if they
-    were measured on this build (the JSON files carry the hash of the kernel sources they belong to)."""
+def profile_figures(workload_key, kernel_names):
+    """HBM traffic and vector-instruction counts per launch from the committed rocprofv3 --pmc summaries
+    (written by paper_2503_16163_amd.profile_summary).  A figure is quoted only for a kernel whose sources still
+    hash to what the file recorded for it."""
     from paper_2503_16163_amd import build as hip_build
-    cur = hip_build.source_hash()
     res = {}
     for key, fname in (("traffic", "traffic.json"), ("valu", "valu.json")):
         path = os.path.join(ROOT, "profiles", fname)
         try:
             d = json.load(open(path))
         except (OSError, ValueError):
-            res[key] = (None, "no profile file")
+            res[key] = ({}, "no profile file")
             continue
-        if d.get("source_hash") != cur:
-            res[key] = (None, f"profiles/{fname} was measured on other kernel sources (hash {str(d.get('source_hash'))[:12]}, "
-                              f"this build {cur[:12]}): not quoted")
-            continue
-        w = d.get(workload, {})
-        res[key] = ({n: w.get(n) for n in kernel_names if w.get(n) is not None}, f"profiles/{fname}: rocprofv3 --pmc on these kernel sources")
+        w, hashes = d.get(workload_key, {}), d.get("kernel_source_hash", {}).get(workload_key, {})
+        tbl, stale = {}, []
+        for n in kernel_names:
+            if w.get(n) is None:
+                continue
+            if hashes.get(n) == hip_build.kernel_source_hash(n.split("+")[0]):
+                tbl[n] = w[n]
+            else:
+                stale.append(n)
+        src = f"profiles/{fname} [{workload_key}]: rocprofv3 --pmc, per launch"
+        if stale:
+            src += "; not quoted, measured on other sources of the kernel: " + ", ".join(stale)
+        if not w:
+            src = f"profiles/{fname} holds no run of {workload_key}"
+        res[key] = (tbl, src)
     return res
 
 
@@ -543,8 +552,13 @@ def main():
     cands = [e for e in kern if e["kernel"] in (one_pass_name, score_name, attend_name)]
     dom = max(cands, key=lambda e: e["avg_us"])
     dom_base = dom["kernel"].split("<")[0] + ("+score" if dom["kernel"] == one_pass_name else "")
-    prof = profile_figures(args.workload, [dom_base, score_name, attend_name, "topk_kernel", "gather_kernel", "attend_combine_kernel"])
+    workload_key = f"{args.workload}:k{k}:g{g}:b{bits}"
+    prof = profile_figures(workload_key, [dom_base, score_name, attend_name, "topk_kernel", "gather_kernel", "attend_combine_kernel"])
     traffic_tbl, traffic_src = prof["traffic"]
+    for e in kern:   # measured HBM bytes per launch beside the algorithmic ones, where the profile covers the kernel
+        base = e["kernel"].split("<")[0] + ("+score" if e["kernel"] == one_pass_name else "")
+        if traffic_tbl.get(base) is not None:
+            e["traffic"] = traffic_tbl[base]
     roofline = {"bound": "hbm", "kernel": dom["kernel"], "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["frac"], "frac_of_measured_stream_peak": dom["frac_of_measured_peak"],
                 "traffic": (traffic_tbl or {}).get(dom_base), "traffic_source": traffic_src,
@@ -597,7 +611,7 @@ def main():
         "kernel_us_no_gather": per_kernel_ng,
         "hbm_gbs_layer": round((2 * packed + pairs) / (us_layer * 1e-6) / 1e9, 1),
         **peaks,
-        "kernels": kern,
+        "kernels": kern, "profile_key": workload_key,
         "score_plus_topk": score_topk,
         "roofline_alu": roofline_alu,
         "kernel_us": breakdown,

@@ -56,6 +56,44 @@ def source_hash():
     return h.hexdigest()
 
 
+def kernel_sources(kernel):
+    """The .hip file that defines __global__ `kernel` and every header it includes, directly or not
+    (base names, sorted); None if no source defines it."""
+    import re
+    pat = re.compile(r"__global__[^;{]*?\b" + re.escape(kernel) + r"\s*\(", re.S)
+    for f in sorted(os.listdir(CSRC)):
+        if not f.endswith(".hip"):
+            continue
+        with open(os.path.join(CSRC, f)) as fh:
+            if not pat.search(fh.read()):
+                continue
+        seen, todo = set(), [os.path.join(CSRC, f)]
+        while todo:
+            path = os.path.normpath(todo.pop())
+            if path in seen or not os.path.exists(path):
+                continue
+            seen.add(path)
+            with open(path) as fh:
+                for inc in re.findall(r'#include\s+"([^"]+)"', fh.read()):
+                    todo.append(os.path.join(os.path.dirname(path), inc))
+        return sorted(seen)
+    return None
+
+
+def kernel_source_hash(kernel):
+    """sha256 over the sources one kernel is compiled from (kernel_sources), so that a figure measured on a
+    kernel stays attributable to it while other kernels change; None for an unknown kernel."""
+    files = kernel_sources(kernel)
+    if files is None:
+        return None
+    h = hashlib.sha256()
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_built():
     """True when libspecache.so exists and was built from the sources as they are now (by content, so that
     a copy of the tree to another machine does not look stale)."""
