@@ -388,7 +388,8 @@ def main():
                          "attention of a chunk in one launch, the logits stay on the chip), select_gather.  split: scoring "
                          "and attention as two calls (with ArgTopK on the gather's stream: score, select_gather, attend).  "
                          "four: quantize_append, score_topk, gather, attend.  auto: one-pass where the one-pass kernel exists "
-                         "(one query head per KV head, 2-bit codes, several layers, speculative), else split")
+                         "(one query head per KV head, 2-bit codes, several layers, speculative) and the arrangement rule "
+                         "puts ArgTopK on the gather's stream (not where the host link bounds the step), else split")
     ap.add_argument("--filler-mb", type=int, default=0,
                     help="EMULATION, not part of the method's path: after every layer's attend, stream this many MB of "
                          "stand-in weights through a plain torch reduction on the main stream (a 7B layer reads about "
@@ -466,8 +467,14 @@ def main():
     one_pass_kernel = G == 1 and bits == 2 and spec and args.select_cache == "lowbit" and not args.vector_alu
     calls = args.calls
     if calls == "auto":
+        # the one-pass call needs ArgTopK on the gather's stream; where the link bounds the step the other
+        # arrangement (ArgTopK on the library's stream) measured faster, and keeps the two-launch form
+        from paper_2503_16163_amd import arrangement
+        on_gather_stream = (args.select_stream == "gather" or
+                            (args.select_stream == "auto" and
+                             arrangement.pick(G, S, k, layers, spec)[0] == arrangement.SELECT_ON_GATHER_STREAM))
         calls = "one-pass" if (one_pass_kernel and layers > 1 and not args.serial_gather and not args.fused_append and
-                               args.select_stream in ("auto", "gather")) else "split"
+                               on_gather_stream) else "split"
     if not spec:
         calls = "four"
 
