@@ -14,6 +14,8 @@ What the line holds beside the contract's fields:
   median_us_layer        median over --median-steps further steps, each bracketed by events on the main stream
   compute_us_layer       the same steps without issuing gathers; gather_hidden_frac = how much of a layer's
                          gather time the step does not pay for
+  host_issue_us_layer    wall time until the last call of the timed steps has returned, per layer-step (the
+                         calls only enqueue; a figure near `value` means the thread waited for room in the queues)
   kernels                per kernel: mean duration (events carried by the kernel's own dispatch packet for the
                          streaming kernels), algorithmic bytes, fraction of the published peak and of the
                          peak measured in this run (hbm_stream_peak_gbs, link_peak_gbs)
@@ -262,6 +264,7 @@ class Run:
         t0 = time.perf_counter()
         for _ in range(n):
             self.step(gather)
+        self.issued_ms = (time.perf_counter() - t0) * 1e3 / n   # the last call has returned; the GPU may still be busy
         self.torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / n
 
@@ -494,6 +497,7 @@ def main():
     for _ in range(args.warmup):
         run.step()
     ms_per_step = run.timed(args.steps)
+    host_issue_us_layer = run.issued_ms * 1e3 / layers
 
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -614,6 +618,7 @@ def main():
         "median_over_steps": args.median_steps if median_us else 0,
         "score_topk_attend_us": round(sta, 3),
         "compute_us_layer": round(compute_us_layer, 3) if compute_us_layer else None,
+        "host_issue_us_layer": round(host_issue_us_layer, 3),
         "gather_hidden_frac": round(hidden, 3) if hidden is not None else None,
         "kernel_us_no_gather": per_kernel_ng,
         "hbm_gbs_layer": round((2 * packed + pairs) / (us_layer * 1e-6) / 1e9, 1),
