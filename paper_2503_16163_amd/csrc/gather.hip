@@ -85,8 +85,7 @@ hipError_t launch_gather(const LayerView& L, int Nq, const int32_t* idx, uint16_
     if (grid > max_grid) grid = max_grid;
     if (grid < 1) return hipSuccess;
     const auto kernel = in_flight == 1 ? gather_kernel<1> : in_flight == 2 ? gather_kernel<2> : in_flight == 3 ? gather_kernel<3> : gather_kernel<4>;
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, stream, (const uint4*)L.host, L.max_seq, L.topk, total, idx,
-                       (uint4*)slot, slot_idx);
+    SPC_LAUNCH(kernel, dim3(grid), dim3(256), stream, (const uint4*)L.host, L.max_seq, L.topk, total, idx, (uint4*)slot, slot_idx);
     return hipGetLastError();
 }
 

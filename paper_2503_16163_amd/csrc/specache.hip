@@ -168,6 +168,28 @@ struct TimedLaunch {
     }
 };
 
+// An ordering event completed by a kernel's own dispatch packet instead of a record behind it: one call
+// into the runtime less per event, and the issuing thread's calls are what bounds a step with little to
+// fetch.  Between arm() and landed() exactly one launcher runs; landed() is false when that launcher
+// launched nothing or when the launch carries timing events (the caller then records the event itself).
+struct CarriedEvent {
+    bool armed = false;
+    CarriedEvent(specache_ctx* c, hipEvent_t ev) {
+        if (c->timing || !ev) return;
+        pending_launch_events() = LaunchEvents{nullptr, ev};
+        armed = true;
+    }
+    bool landed() {
+        if (!armed) return false;
+        armed = false;
+        LaunchEvents& le = pending_launch_events();
+        const bool taken = le.stop == nullptr;
+        le = LaunchEvents{};
+        return taken;
+    }
+    ~CarriedEvent() { if (armed) pending_launch_events() = LaunchEvents{}; }
+};
+
 int check_ctx_layer(specache_ctx* ctx, int32_t layer) {
     if (!ctx) return SPECACHE_EINVAL;
     if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, SPECACHE_EINVAL, "layer out of range");
@@ -211,12 +233,18 @@ void free_all(specache_ctx* ctx) {
 
 // The scoring pass of one layer on stream st: low-bit logits of every query row, selection keys of
 // the last row, and the optional rewrites of those keys (mixed-cache selection, log-probability form).
+// done / done_carried: an event to complete when the keys are final; *done_carried tells whether the scoring
+// launch's own dispatch packet does that (only where no rewrite of the keys follows it).
 int score_phase(specache_ctx* ctx, Layer& L, const void* q, int n_rows, uint32_t* keys, hipStream_t st,
-                const LayerView* fused_view = nullptr) {
+                const LayerView* fused_view = nullptr, hipEvent_t done = nullptr, bool* done_carried = nullptr) {
     if (L.Nq > 0) {
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE, /*kernel_events=*/true);
+        const bool rewrites = (ctx->cfg.select_cache == SPECACHE_SELECT_MIXED && L.last_gather_slot >= 0) ||
+                              (ctx->cfg.select_form == SPECACHE_SELECT_MAX_LOGPROB && L.view.G > 1);
+        CarriedEvent carried(ctx, rewrites ? nullptr : done);
         SPC_HIP(ctx, launch_score(fused_view ? *fused_view : L.view, q, n_rows, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride, keys,
                                   ctx->logit_stride, st));
+        if (done_carried) *done_carried = carried.landed();
         // selection on the mixed cache: the positions staged by the layer's last gather are scored with
         // their 16-bit keys (that slot is the one the coming attend reads; the next gather into it
         // waits for this stream's next selection event, so it cannot overtake the patch)
@@ -256,15 +284,18 @@ int gather_phase(specache_ctx* ctx, Layer& L, int Nq, const int32_t* idx, int sl
     // the slot's previous gather, if it ran on another stream that this one has not waited for
     if (L.slot_filled[slot] && L.gather_stream[slot] != st && !(L.gathered_waited_set[slot] && L.gathered_waited[slot] == st))
         SPC_HIP(ctx, hipStreamWaitEvent(st, L.gathered[slot], 0));
+    bool gathered_carried = false;
     {
         TimedLaunch t(ctx, st, SPECACHE_K_GATHER);
+        CarriedEvent gathered(ctx, L.gathered[slot]);
         // a caller that alternates side streams has two gathers on the link at a time
         const bool link_shared = ctx->last_gather_stream_set && ctx->last_gather_stream != st;
         SPC_HIP(ctx, launch_gather(L.view, Nq, idx, L.slot[slot], L.slot_idx[slot], link_shared, st));
+        gathered_carried = gathered.landed();
         ctx->last_gather_stream = st;
         ctx->last_gather_stream_set = true;
     }
-    SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
+    if (!gathered_carried) SPC_HIP(ctx, hipEventRecord(L.gathered[slot], st));
     L.gather_stream[slot] = st;
     L.gathered_waited_set[slot] = false;
     L.slot_filled[slot] = true;
@@ -555,8 +586,8 @@ static int wait_for_keys_readers(specache_ctx* ctx, Layer& L, hipStream_t st) {
 }
 
 // "scored": what the selection waits for, and what orders a gather after the attends enqueued so far
-static int record_scored(specache_ctx* ctx, Layer& L, int32_t layer, int32_t n_rows, hipStream_t st) {
-    SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
+static int record_scored(specache_ctx* ctx, Layer& L, int32_t layer, int32_t n_rows, hipStream_t st, bool carried = false) {
+    if (!carried) SPC_HIP(ctx, hipEventRecord(L.idx_ready, st));
     L.idx_ready_recorded = true;
     L.idx_ready_stream = st;
     L.select_origin_stream = st;
@@ -581,19 +612,20 @@ static int score_impl(specache_ctx* ctx, int32_t layer, const void* q, int32_t n
     Layer& L = ctx->layers[layer];
     hipStream_t st = (hipStream_t)stream;
     if (int rc = wait_for_keys_readers(ctx, L, st)) return rc;
+    bool carried = false;
     if (k_new) {
         // the scoring launch appends token N: one more workgroup per row copies the pair
         LayerView fused = L.view;
         fused.tail_k = (const uint16_t*)k_new;
         fused.tail_v = (const uint16_t*)v_new;
         fused.tail_N0 = L.N;
-        if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused)) return rc;
+        if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, &fused, L.idx_ready, &carried)) return rc;
         L.N += 1;   // only once the launch that copies the token is enqueued
-    } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st)) {
+    } else if (int rc = score_phase(ctx, L, q, n_rows, L.keys, st, nullptr, L.idx_ready, &carried)) {
         return rc;
     }
     ctx->logits_kept = true;
-    return record_scored(ctx, L, layer, n_rows, st);
+    return record_scored(ctx, L, layer, n_rows, st, carried);
 }
 
 int specache_score(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, void* stream) {
@@ -784,16 +816,19 @@ static int score_attend_impl(specache_ctx* ctx, int32_t layer, const void* k_new
         view.tail_N0 = L.N;
     }
     const int N1 = L.N + (carry ? 1 : 0);
+    bool scored_carried = false;
     {
         TimedLaunch t(ctx, st, SPECACHE_K_SCORE_ATTEND, /*kernel_events=*/true);
+        CarriedEvent scored(ctx, L.idx_ready);
         SPC_HIP(ctx, launch_attend_i8_partial(view, q, N1, L.Nq, ctx->sm_scale, nullptr, ctx->logit_stride,
                                               slot >= 0 ? L.slot[slot] : nullptr, slot >= 0 ? L.slot_idx[slot] : nullptr, k_spec,
                                               v_spec, ctx->scratch, L.keys, ctx->logit_stride, keep ? ctx->logits : nullptr, st));
+        scored_carried = scored.landed();
     }
     L.N = N1;   // only once the launch that copies the token is enqueued
     ctx->logits_kept = keep;
     // the keys are complete here: the selection on the side stream can start while the chunks are merged
-    if (int rc = record_scored(ctx, L, layer, n_rows, st)) return rc;
+    if (int rc = record_scored(ctx, L, layer, n_rows, st, scored_carried)) return rc;
     {
         TimedLaunch t(ctx, st, SPECACHE_K_ATTEND_COMBINE, /*kernel_events=*/true);
         SPC_HIP(ctx, launch_attend(L.view, q, n_rows, L.N, L.Nq, ctx->sm_scale, ctx->logits, ctx->logit_stride,
