@@ -108,6 +108,7 @@ class Run:
         B, Hq, Hkv, S, dtype, bits, g, k, layers = WORKLOADS[args.workload]
         layers = args.layers or layers
         k = args.topk or k
+        S = args.seq or S
         g = args.group or g
         bits = args.bits or bits
         self.B, self.Hq, self.Hkv, self.S, self.dtype, self.bits, self.g, self.k = B, Hq, Hkv, S, dtype, bits, g, k
@@ -115,20 +116,24 @@ class Run:
         self.total_steps = total_steps
         self.spec = args.variant == "speculative"
         side_gathers = self.spec and not args.serial_gather and not args.no_gather
-        # Where ArgTopK runs and how many side streams the gathers alternate over: the measured rule of
-        # paper_2503_16163_amd.arrangement (the full-size parity tests use the same).
-        auto_select, _ = arrangement.pick(self.G, S, k, layers, self.spec, side_gathers)
+        # Where ArgTopK runs, how many side streams the gathers alternate over, whether the scoring launch carries
+        # the append: the measured rule of paper_2503_16163_amd.arrangement (the full-size parity tests use the
+        # same), unless the command line says otherwise.
+        plan = arrangement.plan(B, Hkv, self.G, S, k, layers, bits, self.spec, args.select_cache == "lowbit")
+        planned = plan["calls"] == calls
         if calls == "one-pass":
             async_select = 2          # specache_score_attend leaves its keys to specache_select_gather
         elif calls == "four":
-            async_select = min(auto_select, 1) if args.select_stream == "auto" else {"main": 0, "own": 1, "gather": 1}[args.select_stream]
+            async_select = ((plan["async_select"] if planned else 1 if self.spec and layers > 1 else 0) if args.select_stream == "auto"
+                            else {"main": 0, "own": 1, "gather": 1}[args.select_stream])
         elif args.select_stream == "auto":
-            async_select = auto_select
+            async_select = 2 if side_gathers or args.no_gather else 1
         else:
             async_select = {"main": 0, "own": 1, "gather": 2 if side_gathers else 1}[args.select_stream]
         self.async_select = async_select
         self.carry_append = calls == "one-pass" and (args.append == "carried" or
-                                                     (args.append == "auto" and arrangement.carry_append(self.G, S, k)))
+                                                     (args.append == "auto" and planned and plan["carry_append"]))
+        self.plan_side_streams = plan["side_streams"] if planned else 2
         max_seq = ((S + total_steps + 63) // 64 + 1) * 64
         sc = None
         while sc is None:
@@ -142,7 +147,7 @@ class Run:
                 layers = max(1, layers // 2)   # the pinned host store did not fit: fewer layers
         self.sc, self.layers = sc, layers
         self.main_s = torch.cuda.current_stream()
-        n_side = args.side_streams if args.side_streams > 0 else arrangement.side_streams(async_select, self.G, S, k)
+        n_side = args.side_streams if args.side_streams > 0 else (2 if self.carry_append else self.plan_side_streams)
         self.side_list = [self.main_s] if args.serial_gather else [torch.cuda.Stream() for _ in range(n_side)]
         self.state = {"t": 0}
 
@@ -390,9 +395,10 @@ def main():
                     help="which calls a layer-step is made of.  one-pass: quantize_append, specache_score_attend (scoring and "
                          "attention of a chunk in one launch, the logits stay on the chip), select_gather.  split: scoring "
                          "and attention as two calls (with ArgTopK on the gather's stream: score, select_gather, attend).  "
-                         "four: quantize_append, score_topk, gather, attend.  auto: one-pass where the one-pass kernel exists "
-                         "(one query head per KV head, 2-bit codes, several layers, speculative) and the arrangement rule "
-                         "puts ArgTopK on the gather's stream (not where the host link bounds the step), else split")
+                         "four: quantize_append, score_topk, gather, attend.  auto: what paper_2503_16163_amd.arrangement.plan "
+                         "picks for the shape (one-pass where that kernel exists and the link leaves the main stream a "
+                         "large part of the step; the four calls with ArgTopK on the library's stream where the link alone "
+                         "bounds it; split for the shapes without a one-pass kernel)")
     ap.add_argument("--filler-mb", type=int, default=0,
                     help="EMULATION, not part of the method's path: after every layer's attend, stream this many MB of "
                          "stand-in weights through a plain torch reduction on the main stream (a 7B layer reads about "
@@ -400,6 +406,8 @@ def main():
                          "layer would hide")
     ap.add_argument("--topk", type=int, default=0,
                     help="override k, the number of prefetched pairs per (batch, KV head) (the k sweep of Section 4.4)")
+    ap.add_argument("--seq", type=int, default=0,
+                    help="override S, the number of cached tokens at the start (a multiple of 64)")
     ap.add_argument("--group", type=int, default=0, choices=[0, 32, 64, 128],
                     help="override g, the quantisation group size (the residual becomes max(64, g))")
     ap.add_argument("--bits", type=int, default=0, choices=[0, 1, 2, 4],
@@ -463,6 +471,7 @@ def main():
     B, Hq, Hkv, S, dtype, bits, g, k, layers = WORKLOADS[args.workload]
     layers = args.layers or layers
     k = args.topk or k
+    S = args.seq or S
     g = args.group or g
     bits = args.bits or bits
     G, D = Hq // Hkv, 128
@@ -470,14 +479,16 @@ def main():
     one_pass_kernel = G == 1 and bits == 2 and spec and args.select_cache == "lowbit" and not args.vector_alu
     calls = args.calls
     if calls == "auto":
-        # the one-pass call needs ArgTopK on the gather's stream; where the link bounds the step the other
-        # arrangement (ArgTopK on the library's stream) measured faster, and keeps the two-launch form
         from paper_2503_16163_amd import arrangement
-        on_gather_stream = (args.select_stream == "gather" or
-                            (args.select_stream == "auto" and
-                             arrangement.pick(G, S, k, layers, spec)[0] == arrangement.SELECT_ON_GATHER_STREAM))
-        calls = "one-pass" if (one_pass_kernel and layers > 1 and not args.serial_gather and not args.fused_append and
-                               on_gather_stream) else "split"
+        calls = arrangement.plan(B, Hkv, G, S, k, layers, bits, spec, args.select_cache == "lowbit")["calls"]
+        # options that name another arrangement than the rule's
+        if calls == "one-pass" and (not one_pass_kernel or args.serial_gather or args.fused_append or
+                                    args.select_stream in ("main", "own")):
+            calls = "split"
+        if calls == "four" and args.select_stream == "gather":
+            calls = "one-pass" if one_pass_kernel and not args.fused_append else "split"
+        if calls == "four" and args.fused_append:
+            calls = "split"
     if not spec:
         calls = "four"
 
@@ -563,7 +574,7 @@ def main():
     cands = [e for e in kern if e["kernel"] in (one_pass_name, score_name, attend_name)]
     dom = max(cands, key=lambda e: e["avg_us"])
     dom_base = dom["kernel"].split("<")[0] + ("+score" if dom["kernel"] == one_pass_name else "")
-    workload_key = f"{args.workload}:k{k}:g{g}:b{bits}"
+    workload_key = f"{args.workload}:k{k}:g{g}:b{bits}" + (f":S{S}" if args.seq else "")
     prof = profile_figures(workload_key, [dom_base, score_name, attend_name, "topk_kernel", "gather_kernel", "attend_combine_kernel"])
     traffic_tbl, traffic_src = prof["traffic"]
     for e in kern:   # measured HBM bytes per launch beside the algorithmic ones, where the profile covers the kernel
@@ -607,7 +618,8 @@ def main():
         "dtype_note": "accumulation and outputs are binary32; the contractions run on the matrix cores with int8 operands (packed "
                       "codes, fixed-point multipliers, exact int32 sums) or, with 8 and 16 query rows per KV head, f16 operands",
         "data": "synthetic" if not args.filler_mb else f"synthetic; EMULATED rest of the layer: {args.filler_mb} MB streamed per layer",
-        "config": {"workload": DESCR[args.workload] + (f" [code width overridden: {bits} bits]" if args.bits else ""), "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
+        "config": {"workload": DESCR[args.workload] + (f" [code width overridden: {bits} bits]" if args.bits else "") +
+                               (f" [context overridden: S = {S}]" if args.seq else ""), "layers": layers, "tokens_cached": N, "tokens_quantized": Nq,
                    "residual": run.R, "group": g, "topk": k, "gather": not args.no_gather, "variant": args.variant,
                    "value_covers": "wall time of the whole step / layers: quantize_append + score + top-k + attend, the gather of "
                                    "the next step's pairs on side streams",

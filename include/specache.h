@@ -318,6 +318,15 @@ int specache_debug_logits(specache_ctx* ctx, float* out);
 int specache_debug_poison_slot(specache_ctx* ctx, int32_t layer, int32_t slot, void* stream);
 
 /*
+ * Test hook, process-wide: the nth allocating call (device memory, pinned host memory, events,
+ * streams; counted from 1) of the NEXT specache_create reports out-of-memory without running, so
+ * that the way create backs out of a half-built context (everything allocated so far is freed,
+ * *out stays NULL, ENOMEM) can be tested at every point without exhausting a machine's memory.
+ * 0 switches it off; the setting is consumed by that one create.  Errors: EINVAL (nth < 0).
+ */
+int specache_debug_fail_alloc(int32_t nth);
+
+/*
  * Measurement hook, process-wide: which formulation of the two streaming kernels runs for one
  * query head per KV head and two query rows.  0 (the default): the integer matrix cores; a flag
  * set: that kernel's vector-ALU formulation instead (same results to the parity bars), so that

@@ -18,7 +18,7 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
            "specache_score", "specache_select_gather", "specache_append_score",
-           "specache_attend", "specache_score_attend", "specache_append_score_attend", "specache_attend_static", "specache_debug_poison_slot", "specache_debug_kernel_choice", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
+           "specache_attend", "specache_score_attend", "specache_append_score_attend", "specache_attend_static", "specache_debug_poison_slot", "specache_debug_fail_alloc", "specache_debug_kernel_choice", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
            "specache_timing", "specache_measure_hbm_read", "specache_measure_link"]
 
 
@@ -69,6 +69,7 @@ def lib():
         L.specache_append_score_attend.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, i32, vp, vp]
         L.specache_debug_poison_slot.argtypes = [vp, i32, i32, vp]
         L.specache_debug_kernel_choice.argtypes = [i32]
+        L.specache_debug_fail_alloc.argtypes = [i32]
         L.specache_export_quantized.argtypes = [vp, i32] + [vp] * 6
         L.specache_export_rows.argtypes = [vp, i32, i32, i32, vp]
         L.specache_debug_logits.argtypes = [vp, vp]
@@ -110,6 +111,13 @@ def plan_append(residual, group, n_tokens, n_quantized, n_new):
 
 
 SCORE_ON_VECTOR_ALU, ATTEND_ON_VECTOR_ALU, KEEP_ONE_PASS_LOGITS = 1, 2, 4
+
+
+def debug_fail_alloc(nth):
+    """The nth allocating call of the next specache_create fails (0: off)."""
+    rc = lib().specache_debug_fail_alloc(nth)
+    if rc != OK:
+        raise SpeCacheError(rc, "specache_debug_fail_alloc")
 
 
 def debug_kernel_choice(flags):

@@ -71,6 +71,7 @@ struct Layer {
 };
 
 thread_local std::string g_create_error;
+int g_fail_alloc_at = 0;   // specache_debug_fail_alloc
 
 }  // namespace
 
@@ -397,10 +398,14 @@ int specache_create(const specache_config* cfg, specache_ctx** out) {
         delete ctx;
         return rc;
     };
-#define SPC_ALLOC(call)                               \
-    do {                                              \
-        hipError_t e_ = (call);                       \
-        if (e_ != hipSuccess) return bail(e_, #call); \
+    // specache_debug_fail_alloc: the n-th allocating call of this create reports hipErrorOutOfMemory instead of running
+    int fail_at = g_fail_alloc_at;
+    g_fail_alloc_at = 0;
+    int alloc_no = 0;
+#define SPC_ALLOC(call)                                                             \
+    do {                                                                            \
+        hipError_t e_ = ++alloc_no == fail_at ? hipErrorOutOfMemory : (call);       \
+        if (e_ != hipSuccess) return bail(e_, #call);                               \
     } while (0)
 
     // The events only order streams of this device among themselves and the host never waits on
@@ -857,6 +862,12 @@ int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int3
     if (int rc = static_scratch_of_current_device(ctx, &base)) return rc;
     const AttendScratch st{base, nullptr, 0};
     return attend_impl(ctx, layer, q, n_rows, k_spec, v_spec, slot, out, stream, &st);
+}
+
+int specache_debug_fail_alloc(int32_t nth) {
+    if (nth < 0) return SPECACHE_EINVAL;
+    g_fail_alloc_at = nth;
+    return SPECACHE_OK;
 }
 
 int specache_debug_kernel_choice(int32_t flags) {

@@ -295,13 +295,14 @@ hipError_t launch_ranges(int rows, int n, const TopkIo& io, int k, const uint32_
 
 }  // namespace
 
-// Rows longer than the registers of one workgroup hold (65536 keys) are split into ranges of
-// about kTopkPartKeys keys, as many as keep the candidate list of the second launch within
-// one workgroup's registers.
-constexpr int kTopkRegisterKeys = 65536, kTopkPartKeys = 16384;
+// One workgroup's registers hold 65536 keys, but its time grows faster than the row (32 rows, k = 256, alone:
+// 17 us for 32768 keys, 34 for 49152, 61 and more for 65536), so rows beyond kTopkSingleLaunchKeys are split
+// into ranges of about kTopkPartKeys keys, as many as keep the candidate list of the second launch within
+// one workgroup's registers: two launches of 12 to 15 us each.
+constexpr int kTopkRegisterKeys = 65536, kTopkPartKeys = 16384, kTopkSingleLaunchKeys = 40960;
 
 int topk_parts(int Nq, int k) {
-    if (Nq <= kTopkRegisterKeys || k <= 0) return 1;
+    if (Nq <= kTopkSingleLaunchKeys || k <= 0) return 1;
     int parts = (Nq + kTopkPartKeys - 1) / kTopkPartKeys;
     const int most = kTopkRegisterKeys / k;
     parts = parts < most ? parts : most;

@@ -78,6 +78,8 @@ int main() {
     REQUIRE(specache_score(nullptr, 0, nullptr, 2, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_append_score(nullptr, 0, nullptr, nullptr, nullptr, 2, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_select_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);
+    REQUIRE(specache_debug_fail_alloc(-1) == SPECACHE_EINVAL);
+    REQUIRE(specache_debug_fail_alloc(0) == SPECACHE_OK);
     REQUIRE(specache_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_attend(nullptr, 0, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_score_attend(nullptr, 0, nullptr, 2, nullptr, nullptr, -1, nullptr, nullptr) == SPECACHE_EINVAL);

@@ -801,3 +801,33 @@ def test_full_size_sampled(name):
         print(name, c.stats)
     finally:
         c.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("async_select", [0, 1, 2])
+def test_create_backs_out_of_every_failed_allocation(async_select):
+    """specache_create with its n-th allocating call failing (device memory, the pinned host store, events, the
+    library's stream), for every n: ENOMEM, no context, nothing left allocated; the create after it works."""
+    import torch
+    args = (2, 1, 4, 2, 2, 32, 70016, 64, synth.FP16)        # long enough for the two-launch ArgTopK's candidate arrays
+    binding.SpeCache(*args, async_select=async_select).close()     # the library's code and static data are loaded
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    n = 1
+    while True:
+        binding.debug_fail_alloc(n)
+        try:
+            sc = binding.SpeCache(*args, async_select=async_select)
+        except binding.SpeCacheError as e:
+            assert e.code == binding.ENOMEM, (n, str(e))
+            n += 1
+            assert n < 200
+            continue
+        sc.close()            # n is past the last allocating call: the hook was consumed without effect
+        break
+    assert n > 40, n          # two layers: at least 18 allocating calls each
+    torch.cuda.synchronize()
+    assert abs(torch.cuda.mem_get_info()[0] - free0) < (64 << 20), "device memory of a failed create was not returned"
+    binding.debug_fail_alloc(0)
+    sc = binding.SpeCache(*args, async_select=async_select)
+    sc.close()

@@ -55,10 +55,13 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
     B, Hq, Hkv, S, dtype, bits, g, k, layers = shape or SHAPES[name]
     G, D, R = Hq // Hkv, 128, max(64, g)
     seed = 5000 + S + k
-    async_select, n_side = arrange or arrangement.pick(G, S, k, layers)
-    if one_pass and shape is None:
-        async_select = 2          # specache_score_attend leaves its keys to specache_select_gather
-        n_side = arrangement.side_streams(async_select, G, S, k)
+    plan = arrangement.plan(B, Hkv, G, S, k, layers, bits)
+    async_select, n_side = arrange or (plan["async_select"], plan["side_streams"])
+    if arrange is None and not one_pass and not fused_append:
+        # no arrangement asked for: the calls bench.py times for this shape
+        one_pass, fused_append = plan["calls"] == "one-pass", plan["carry_append"]
+    if (one_pass or fused_append) and arrange is None and async_select != 2:
+        async_select, n_side = 2, 2     # these calls leave their keys to specache_select_gather
     if fused_append or one_pass:
         assert async_select == 2
     max_seq = ((S + steps + 63) // 64 + 1) * 64
@@ -173,7 +176,16 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", list(SHAPES))
 def test_full_size_all_rows_in_the_timed_arrangement(name):
+    """Every shape in the arrangement paper_2503_16163_amd.arrangement.plan picks for it, which is what bench.py times."""
     run_free_running(name)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["config2", "M0_7B_32k"])
+def test_full_size_all_rows_two_launches_selection_on_the_gathers_stream(name):
+    """specache_score + specache_select_gather + specache_attend (bench.py --calls split) where the rule picks the
+    one-pass call."""
+    run_free_running(name, arrange=(2, 3))
 
 
 @pytest.mark.timeout(600)
