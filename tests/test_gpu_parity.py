@@ -218,6 +218,30 @@ def test_long_decode_crosses_flushes(bits, g, R):
         c.close()
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("dtype,g,R", [(synth.FP16, 32, 64), (synth.BF16, 64, 128)])
+def test_one_call_layer_step_over_many_steps_and_chunk_boundaries(dtype, g, R):
+    """720 decode steps through specache_append_score_attend + specache_select_gather from a 900-token prompt:
+    the quantised prefix grows across two 512-token chunk boundaries (1024, 1536), the residual ring wraps many
+    times, every g-th step flushes (the append then runs as a launch of its own).  Every step against the oracle."""
+    from tests.harness import Case
+    binding.debug_kernel_choice(binding.KEEP_ONE_PASS_LOGITS)     # for the steps whose logits are compared
+    c = Case(1, 2, 2, 900, dtype, 2, g, 48, R=R, seed=6400 + g, async_select=2, one_pass=True, fused_append=True, max_seq=1664)
+    try:
+        c.load()
+        n0, _ = c.check_quantized()
+        for t in range(720):
+            c.append_token(t)
+            c.decode_step(check_logits=(t % 16 == 0))
+        n1, nq1 = c.check_quantized()
+        assert n1 == n0 + 720 and nq1 >= 1536
+        c.check_offload(first=c.S, count=720)
+        print(c.stats)
+    finally:
+        c.close()
+        binding.debug_kernel_choice(0)
+
+
 def test_streamed_load_equals_bulk_load():
     """Loading the prompt in uneven pieces and token by token reaches the same quantised state."""
     from tests.harness import Case
