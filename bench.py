@@ -476,7 +476,7 @@ def main():
     bits = args.bits or bits
     G, D = Hq // Hkv, 128
     spec = args.variant == "speculative"
-    one_pass_kernel = G == 1 and bits == 2 and spec and args.select_cache == "lowbit" and not args.vector_alu
+    one_pass_kernel = G == 1 and bits in (1, 2) and spec and args.select_cache == "lowbit" and not args.vector_alu
     calls = args.calls
     if calls == "auto":
         from paper_2503_16163_amd import arrangement
@@ -536,7 +536,7 @@ def main():
                   "score_i8_kernel" if (G == 1 and spec and args.vector_alu not in ("score", "both"))
                   else "score_mfma_kernel" if n_q_rows % 8 == 0 else "score_kernel")
     attend_name = ("attend4_partial_kernel" if bits == 4 else
-                   "attend_i8_kernel" if (G == 1 and spec and bits == 2 and args.vector_alu not in ("attend", "both")) else "attend_partial_kernel")
+                   "attend_i8_kernel" if (G == 1 and spec and bits in (1, 2) and args.vector_alu not in ("attend", "both")) else "attend_partial_kernel")
     one_pass_name = "attend_i8_kernel<scoring pass in front>"
     stream_peak = peaks["hbm_stream_peak_gbs"]
     link_peak = peaks["link_peak_gbs"]

@@ -7,7 +7,7 @@ The rule compares two times that follow from the shape:
 
   link_us  what one layer's prefetch needs on the host link: rows x k x 512 bytes at the rate
            specache_measure_link reports on these machines (57.5 GB/s);
-  main_us  what the caller's stream needs for one layer with one query head per KV head and 2-bit codes,
+  main_us  what the caller's stream needs for one layer with one query head per KV head and 1- or 2-bit codes,
            where scoring and attention are one launch (specache_score_attend): 22 us + 19.8 us per million
            (row, cached token) pairs, and never less than the 33 us the issuing thread needs for the
            runtime calls of a layer-step (measured without gathers: 16k tokens 33, 32k 42, 48k 52, 64k 63 us).
@@ -25,7 +25,7 @@ The rule compares two times that follow from the shape:
                            its selection is done instead of behind the previous gather of its stream (64k
                            tokens, k = 384: 118 us per layer against 147 to 169).
 
-One query head per KV head without the one-launch kernel (1-bit or 4-bit codes, selection on the mixed cache):
+One query head per KV head without the one-launch kernel (4-bit codes, selection on the mixed cache):
 the same ladder with score + select_gather + attend in place of the one-launch call.  Several query heads per
 KV head: score + select_gather + attend with ArgTopK on the gather's stream and two side streams, which
 measured best or level with the best at every shape tried (8B-class shape with 8k and 32k tokens and k = 256 to
@@ -60,7 +60,7 @@ def plan(B, Hkv, G, S, k, layers, bits=2, speculative=True, select_lowbit=True):
         return dict(calls="four", async_select=SELECT_ON_CALLER, side_streams=1, carry_append=False)
     if G > 1:
         return dict(calls="split", async_select=SELECT_ON_GATHER_STREAM, side_streams=2, carry_append=False)
-    one_pass = bits == 2 and select_lowbit      # the shapes specache_score_attend has its one-launch kernel for
+    one_pass = bits in (1, 2) and select_lowbit      # the shapes specache_score_attend has its one-launch kernel for
     if link_us(rows, k) <= 0.9 * main_us(rows, S):
         return dict(calls="one-pass" if one_pass else "split", async_select=SELECT_ON_GATHER_STREAM, side_streams=2,
                     carry_append=one_pass)

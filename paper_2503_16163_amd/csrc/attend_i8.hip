@@ -1,5 +1,5 @@
 // Mixed attention of Eq. 1 (Section 3.3) for one query head per KV head and the two query rows
-// of a decode step, 2-bit values: the value side on the integer matrix cores, alone
+// of a decode step, 1- or 2-bit values: the value side on the integer matrix cores, alone
 // (attend_i8_kernel, after a scoring pass that left the logits in memory) or in one pass with the
 // low-bit scoring of Appendix A "Decoding" (the same kernel with the scoring pass in front: the logits never leave the chip).
 //
@@ -19,6 +19,10 @@
 //       With two rows, two groups and four planes the 16 columns are exactly full; of every result
 //       the half whose column group matches the row's channel group is used;
 //   C = int32, exact.  The planes are recombined in fp32 when the workgroup merges its waves.
+// With 1-bit codes a byte holds 8 channels of a token and 16 code lanes are all 128 channels: the masks are
+// 0x01010101 << j on the word and on the word shifted by 4 (operands code x 1, 2, 4, 8), eight products per
+// token step, each run against the columns of either channel half; of a product's 16 rows the 8 code lanes
+// of that half are kept.
 // The zero-point term and the row sums stay on the vector ALUs (one multiply-add per token, group
 // and row).
 //
@@ -68,16 +72,16 @@ struct WaveOut {
 // requests consecutive 16 bytes of it (so that a load instruction covers whole cache lines) and the wave
 // then hands the words through its LDS area to the lanes that use them: the groups of channel set h for
 // the lane's four tokens (value_meta_exchange).
-template <int GROUP>
+template <int GROUP, int BITS>
 struct ValueLoads {
     static constexpr int M = kD / GROUP, MPL = M >= 2 ? M / 2 : 1;
-    uint4 vw[2][2];
+    uint4 vw[2][BITS];           // [token step][channel set] with 2 bits; one word per token step holds all channels with 1
     uint4 raw[M == 4 ? 2 : 1];
     uint32_t mw[4][MPL];
 };
 
-template <int GROUP>
-__device__ __forceinline__ void value_loads(const LayerView& L, int row, int c0, int w0, int nw, int lane, ValueLoads<GROUP>& v) {
+template <int GROUP, int BITS>
+__device__ __forceinline__ void value_loads(const LayerView& L, int row, int c0, int w0, int nw, int lane, ValueLoads<GROUP, BITS>& v) {
     constexpr int M = kD / GROUP;
     const int sg = lane >> 4, l16 = lane & 15;
     const bool live = 32 * sg < nw;
@@ -93,24 +97,25 @@ __device__ __forceinline__ void value_loads(const LayerView& L, int row, int c0,
         v.raw[0] = (32 * sg + 4 * (lane & 7)) < nw ? *reinterpret_cast<const uint4*>(vm_row + tok + 4 * (lane & 7)) : zero;
     }
     // codes: lane (il = lane % 16, tg = lane / 16) reads, for token step ks and channel set s, the 16 tokens
-    // 64 ks + 16 tg .. + 15 of code lane 16 s + il (channels 4 (16 s + il) .. + 3)
+    // 64 ks + 16 tg .. + 15 of code lane 16 s + il (channels 4 (16 s + il) .. + 3); with 1-bit codes of code
+    // lane il (channels 8 il .. + 7)
     const int il = lane & 15, tg = lane >> 4;
     const uint8_t* vc_row = L.vc + (size_t)row * L.vc_stride;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
         const int tw = 64 * ks + 16 * tg;                                  // inside the wave
         const size_t t16 = tw < nw ? (size_t)c0 + w0 + tw : (size_t)c0;    // past the end: the chunk's first tokens (p = 0 there)
-        const uint8_t* base = vc_row + (t16 / kBlockTokens) * code_block_bytes(2) + ((t16 / 16) & 1) * 512;
+        const uint8_t* base = vc_row + (t16 / kBlockTokens) * code_block_bytes(BITS) + ((t16 / 16) & 1) * (256 * BITS);
 #pragma unroll
-        for (int s = 0; s < 2; ++s) v.vw[ks][s] = *reinterpret_cast<const uint4*>(base + (16 * s + il) * 16);
+        for (int s = 0; s < BITS; ++s) v.vw[ks][s] = *reinterpret_cast<const uint4*>(base + (16 * s + il) * 16);
     }
 }
 
 // Metadata words from the lanes that loaded them to the lanes that use them, through the wave's LDS area
 // (free at that point): [h][128 tokens] cells of the groups of channel set h, written per token, read as the
 // lane's four consecutive tokens.
-template <int GROUP>
-__device__ __forceinline__ void value_meta_exchange(ValueLoads<GROUP>& v, int lane, uint8_t* area) {
+template <int GROUP, int BITS>
+__device__ __forceinline__ void value_meta_exchange(ValueLoads<GROUP, BITS>& v, int lane, uint8_t* area) {
     constexpr int M = kD / GROUP;
     const int sg = lane >> 4, l16 = lane & 15, h = (lane >> 3) & 1, t0 = 32 * sg + 4 * (lane & 7);
     if constexpr (M == 4) {
@@ -165,9 +170,9 @@ __device__ __forceinline__ void wave_bitmap_apply(const int t[4], int nw, int la
 // The value side of one wave: softmax numerators relative to the wave's maximum, B operands, zero-point and
 // row sums, the contraction, and the results left in the wave's area for the merge.  lgv: the logits of the
 // lane's four tokens of row h (-inf where not a candidate).  nw > 0.
-template <int GROUP, bool BF16>
-__device__ __forceinline__ void value_wave(const ValueLoads<GROUP>& v, float lgv[4], int wave, int lane, uint8_t* area,
-                                           WaveOut& out) {
+template <int GROUP, int BITS, bool BF16>
+__device__ __forceinline__ void value_wave(const ValueLoads<GROUP, BITS>& v, float lgv[4], bool one_bit_plain, int wave, int lane,
+                                           uint8_t* area, WaveOut& out) {
     constexpr int M = kD / GROUP;                 // value groups per token: 4, 2, 1
     constexpr int MPL = M >= 2 ? M / 2 : 1;       // groups a lane prepares
     constexpr int RPL = M >= 2 ? 2 : 1;           // rows a lane prepares (one group only: each lane its own row)
@@ -209,7 +214,7 @@ __device__ __forceinline__ void value_wave(const ValueLoads<GROUP>& v, float lgv
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int ml = 0; ml < MPL; ++ml) {
-            derive_scale_zero<2>(widen16<BF16>(v.mw[j][ml] & 0xFFFFu), widen16<BF16>(v.mw[j][ml] >> 16), false, sc[j][ml], zp[j][ml]);
+            derive_scale_zero<BITS>(widen16<BF16>(v.mw[j][ml] & 0xFFFFu), widen16<BF16>(v.mw[j][ml] >> 16), one_bit_plain, sc[j][ml], zp[j][ml]);
             smax = fmaxf(smax, sc[j][ml]);
         }
     const float top = wave_max(smax);
@@ -270,38 +275,79 @@ __device__ __forceinline__ void value_wave(const ValueLoads<GROUP>& v, float lgv
     }
     wave_sync();
 
-    // the contraction, one channel set at a time: per token step one B operand and four masks of the code bytes
+    // the contraction, one channel set at a time: per token step one B operand and the masks of the code bytes
     const int bn = lane & 15;
     const int brow = bn >> 3, bml = (bn >> 2) & 1, bpp = bn & 3;
-    // Result register e of lane (column bn, quarter tg) is MFMA row 4 tg + e: code lane 16 s + 4 tg + e, i.e.
-    // channel 64 s + 16 tg + 4 e + j, whose value group is 2 s + tg / 2 (g = 32), s (g = 64) or 0.  The columns
-    // of that group are kept: [row][plane][j][16 rows] int32 per set.
-    const bool keep = M == 4 ? bml == (tg >> 1) : bml == 0;
+    if constexpr (BITS == 2) {
+        // Result register e of lane (column bn, quarter tg) is MFMA row 4 tg + e: code lane 16 s + 4 tg + e, i.e.
+        // channel 64 s + 16 tg + 4 e + j, whose value group is 2 s + tg / 2 (g = 32), s (g = 64) or 0.  The columns
+        // of that group are kept: [row][plane][j][16 rows] int32 per set.
+        const bool keep = M == 4 ? bml == (tg >> 1) : bml == 0;
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
-        v4i acc[4];
+        for (int s = 0; s < 2; ++s) {
+            v4i acc[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = (v4i){0, 0, 0, 0};
-        uint8_t* set = area + s * kSetBytes;
+            for (int j = 0; j < 4; ++j) acc[j] = (v4i){0, 0, 0, 0};
+            uint8_t* set = area + s * kSetBytes;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const v4i b = *reinterpret_cast<const v4i*>(set + ((brow * 2 + (M == 4 ? bml : 0)) * 4 + bpp) * kColStride + 64 * ks + 16 * tg);
-            const uint4 w = v.vw[ks][s];
-            const uint4 t = make_uint4(w.x >> 4, w.y >> 4, w.z >> 4, w.w >> 4);
-            const v4i a0 = {(int)(w.x & 0x03030303u), (int)(w.y & 0x03030303u), (int)(w.z & 0x03030303u), (int)(w.w & 0x03030303u)};
-            const v4i a1 = {(int)(w.x & 0x0C0C0C0Cu), (int)(w.y & 0x0C0C0C0Cu), (int)(w.z & 0x0C0C0C0Cu), (int)(w.w & 0x0C0C0C0Cu)};
-            const v4i a2 = {(int)(t.x & 0x03030303u), (int)(t.y & 0x03030303u), (int)(t.z & 0x03030303u), (int)(t.w & 0x03030303u)};
-            const v4i a3 = {(int)(t.x & 0x0C0C0C0Cu), (int)(t.y & 0x0C0C0C0Cu), (int)(t.z & 0x0C0C0C0Cu), (int)(t.w & 0x0C0C0C0Cu)};
-            acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b, acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2, b, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a3, b, acc[3], 0, 0, 0);
+            for (int ks = 0; ks < 2; ++ks) {
+                const v4i b = *reinterpret_cast<const v4i*>(set + ((brow * 2 + (M == 4 ? bml : 0)) * 4 + bpp) * kColStride + 64 * ks + 16 * tg);
+                const uint4 w = v.vw[ks][s];
+                const uint4 t = make_uint4(w.x >> 4, w.y >> 4, w.z >> 4, w.w >> 4);
+                const v4i a0 = {(int)(w.x & 0x03030303u), (int)(w.y & 0x03030303u), (int)(w.z & 0x03030303u), (int)(w.w & 0x03030303u)};
+                const v4i a1 = {(int)(w.x & 0x0C0C0C0Cu), (int)(w.y & 0x0C0C0C0Cu), (int)(w.z & 0x0C0C0C0Cu), (int)(w.w & 0x0C0C0C0Cu)};
+                const v4i a2 = {(int)(t.x & 0x03030303u), (int)(t.y & 0x03030303u), (int)(t.z & 0x03030303u), (int)(t.w & 0x03030303u)};
+                const v4i a3 = {(int)(t.x & 0x0C0C0C0Cu), (int)(t.y & 0x0C0C0C0Cu), (int)(t.z & 0x0C0C0C0Cu), (int)(t.w & 0x0C0C0C0Cu)};
+                acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2, b, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a3, b, acc[3], 0, 0, 0);
+            }
+            wave_sync();   // every lane has read the set's B operands: its columns are free for the results
+            if (keep) {
+                int* res = reinterpret_cast<int*>(set);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(res + (((brow * 4 + bpp) * 4 + j) * 16 + 4 * tg)) = acc[j];
+            }
         }
-        wave_sync();   // every lane has read the set's B operands: its columns are free for the results
-        if (keep) {
-            int* res = reinterpret_cast<int*>(set);
+    } else {
+        // MFMA row 4 tg + e is code lane 4 tg + e, channels 8 (4 tg + e) .. + 7: channel half (set) tg / 2, value
+        // group tg (g = 32), tg / 2 (g = 64) or 0.  Each set's columns run against all 16 code lanes and the 8 of
+        // the set are kept: [row][plane][j = 0..7][8 code lanes] int32 per set, the size of the 2-bit results.
 #pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<v4i*>(res + (((brow * 4 + bpp) * 4 + j) * 16 + 4 * tg)) = acc[j];
+        for (int s = 0; s < 2; ++s) {
+            uint8_t* set = area + s * kSetBytes;
+            v4i b[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                b[ks] = *reinterpret_cast<const v4i*>(set + ((brow * 2 + (M == 4 ? bml : 0)) * 4 + bpp) * kColStride + 64 * ks + 16 * tg);
+            wave_sync();   // every lane holds the set's B operands: its columns are free for the results
+            const bool keep = (tg >> 1) == s && (M == 4 ? bml == (tg & 1) : bml == 0);
+#pragma unroll
+            for (int jh = 0; jh < 2; ++jh) {
+                v4i acc[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = (v4i){0, 0, 0, 0};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) {
+                    uint4 w = v.vw[ks][0];
+                    if (jh) w = make_uint4(w.x >> 4, w.y >> 4, w.z >> 4, w.w >> 4);
+                    const v4i a0 = {(int)(w.x & 0x01010101u), (int)(w.y & 0x01010101u), (int)(w.z & 0x01010101u), (int)(w.w & 0x01010101u)};
+                    const v4i a1 = {(int)(w.x & 0x02020202u), (int)(w.y & 0x02020202u), (int)(w.z & 0x02020202u), (int)(w.w & 0x02020202u)};
+                    const v4i a2 = {(int)(w.x & 0x04040404u), (int)(w.y & 0x04040404u), (int)(w.z & 0x04040404u), (int)(w.w & 0x04040404u)};
+                    const v4i a3 = {(int)(w.x & 0x08080808u), (int)(w.y & 0x08080808u), (int)(w.z & 0x08080808u), (int)(w.w & 0x08080808u)};
+                    acc[0] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b[ks], acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b[ks], acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a2, b[ks], acc[2], 0, 0, 0);
+                    acc[3] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a3, b[ks], acc[3], 0, 0, 0);
+                }
+                if (keep) {
+                    int* res = reinterpret_cast<int*>(set);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        *reinterpret_cast<v4i*>(res + (((brow * 4 + bpp) * 8 + 4 * jh + j) * 8 + 4 * (tg & 1))) = acc[j];
+                }
+            }
         }
     }
 }
@@ -317,19 +363,23 @@ __device__ __forceinline__ void empty_wave(int wave, int lane, WaveOut& out) {
 }
 
 // Merge of the four waves of a chunk (after a workgroup barrier): thread = (row r, channel c).
-template <int GROUP>
+template <int GROUP, int BITS>
 __device__ __forceinline__ void merge_waves(const uint8_t* areas, int area_stride, const WaveOut& out, int tid, float* po,
                                             float* pml) {
     constexpr int M = kD / GROUP, MPL = M >= 2 ? M / 2 : 1;
     const int r = tid >> 7, c = tid & 127;
-    const int s = c >> 6, i = (c >> 2) & 15, j = c & 3;
+    // where the channel's sums sit in its set's results: 2 bits [row][plane][j = c % 4][code lane (c / 4) % 16],
+    // 1 bit [row][plane][j = c % 8][code lane (c / 8) % 8]
+    const int s = c >> 6, i = BITS == 2 ? (c >> 2) & 15 : (c >> 3) & 7, j = BITS == 2 ? c & 3 : c & 7;
+    constexpr int NJ = BITS == 2 ? 4 : 8, NI = BITS == 2 ? 16 : 8;
     const int m = c / GROUP;
     const int hh = M >= 2 ? m / MPL : r, zi = M >= 2 ? r * MPL + m % MPL : 0;   // where the zero-point sum of (r, m) sits
     float mmax = -INFINITY;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) mmax = fmaxf(mmax, out.m[w][r]);
     float o = 0.0f, lsum = 0.0f;
-    const float jscale = (j & 1) ? 0.25f : 1.0f;      // the codes of odd channels arrive as 4 x code
+    // the masks leave a code where it sits in its nibble: 4 x code for odd channels (2 bits), 2^(c % 4) x code (1 bit)
+    const float jscale = BITS == 2 ? ((j & 1) ? 0.25f : 1.0f) : __uint_as_float((uint32_t)(127 - (j & 3)) << 23);
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
         const float mwv = out.m[w][r];
@@ -337,7 +387,7 @@ __device__ __forceinline__ void merge_waves(const uint8_t* areas, int area_strid
         const int* res = reinterpret_cast<const int*>(areas + w * area_stride + s * kSetBytes);
         float f[4];
 #pragma unroll
-        for (int pp = 0; pp < 4; ++pp) f[pp] = (float)res[((r * 4 + pp) * 4 + j) * 16 + i];
+        for (int pp = 0; pp < 4; ++pp) f[pp] = (float)res[((r * 4 + pp) * NJ + j) * NI + i];
         float t = __builtin_fmaf(f[1], 256.0f, f[0]);
         t = __builtin_fmaf(f[2], 65536.0f, t);
         t = __builtin_fmaf(f[3], 16777216.0f, t);
@@ -386,7 +436,7 @@ __device__ __forceinline__ void chunk_bitmap(const AttendArgs& A, int topk, int 
 
 // Registers: the pass that also scores needs 84 to 88 (five waves per SIMD); compiled for six or eight it
 // spills and runs slower (measured at the 7B shape: 28.6 us, 32 with two registers spilled, 58 with 34).
-template <int GROUP, bool BF16, bool FUSED>
+template <int GROUP, int BITS, bool BF16, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attend_i8_kernel(LayerView L, AttendArgs A, float sm_scale, uint32_t* __restrict__ keys,
                                                              size_t key_stride) {
     constexpr int NR = 2;
@@ -442,7 +492,7 @@ __global__ __launch_bounds__(kThreads) void attend_i8_kernel(LayerView L, Attend
     if (!wave_maps) chunk_bitmap(A, L.topk, row, c0, n, tid, maskbits);
 
     if (nw > 0) {   // wave-uniform
-        ValueLoads<GROUP> v;
+        ValueLoads<GROUP, BITS> v;
         float lgv[4];
         // everything this wave reads from global memory is requested before the first wait on any of it
         int ti[4];
@@ -450,16 +500,16 @@ __global__ __launch_bounds__(kThreads) void attend_i8_kernel(LayerView L, Attend
         if constexpr (!FUSED) {
             float4 lg4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
             if (live) lg4 = *reinterpret_cast<const float4*>(A.logits + ((size_t)row * NR + h) * A.logit_stride + c0 + w0 + t0);
-            value_loads<GROUP>(L, row, c0, w0, nw, lane, v);
+            value_loads<GROUP, BITS>(L, row, c0, w0, nw, lane, v);
             if (wave_maps) wave_bitmap_apply(ti, nw, lane, maskbits + 4 * wave);
             lgv[0] = lg4.x; lgv[1] = lg4.y; lgv[2] = lg4.z; lgv[3] = lg4.w;
         } else {
             // the low-bit logits of the wave's tokens (Appendix A "Decoding": A = Q K^T on C'); the value-side loads
             // are requested once the scoring operands are built and travel while the scoring contraction runs
-            score_i8_wave<2, BF16>(L, A.q, row, chunk, wave, lane, A.Nq / kBlockTokens, sm_scale, reinterpret_cast<uint32_t*>(area),
+            score_i8_wave<BITS, BF16>(L, A.q, row, chunk, wave, lane, A.Nq / kBlockTokens, sm_scale, reinterpret_cast<uint32_t*>(area),
                                    fin[wave], lgv,
                                    [&]() { if (wave_maps) wave_bitmap_apply(ti, nw, lane, maskbits + 4 * wave); },
-                                   [&]() { value_loads<GROUP>(L, row, c0, w0, nw, lane, v); });
+                                   [&]() { value_loads<GROUP, BITS>(L, row, c0, w0, nw, lane, v); });
             if (live) {
                 if (h == 1)   // the speculative row ranks the positions
                     *reinterpret_cast<uint4*>(keys + (size_t)row * key_stride + c0 + w0 + t0) =
@@ -470,22 +520,22 @@ __global__ __launch_bounds__(kThreads) void attend_i8_kernel(LayerView L, Attend
             }
             wave_sync();   // the scoring exchange is over: the area now serves the value side
         }
-        value_meta_exchange<GROUP>(v, lane, area);
+        value_meta_exchange<GROUP, BITS>(v, lane, area);
         const uint32_t mbits = maskbits[4 * wave + sg] >> (4 * (lane & 7));
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (!live || ((mbits >> j) & 1u)) lgv[j] = -INFINITY;
-        value_wave<GROUP, BF16>(v, lgv, wave, lane, area, wout);
+        value_wave<GROUP, BITS, BF16>(v, lgv, L.one_bit_plain, wave, lane, area, wout);
     } else {
         empty_wave(wave, lane, wout);
     }
     __syncthreads();
-    merge_waves<GROUP>(reinterpret_cast<const uint8_t*>(smem), kAreaBytes, wout, tid, po, pml);
+    merge_waves<GROUP, BITS>(reinterpret_cast<const uint8_t*>(smem), kAreaBytes, wout, tid, po, pml);
 }
 
 }  // namespace
 
-bool attend_uses_int8_matrix_cores(const LayerView& L, int n_rows) { return L.G == 1 && n_rows == 2 && L.bits == 2; }
+bool attend_uses_int8_matrix_cores(const LayerView& L, int n_rows) { return L.G == 1 && n_rows == 2 && (L.bits == 2 || L.bits == 1); }
 
 // keys != null: the scoring pass runs inside the launch (logits are not read; they are written to logits_out if set)
 hipError_t launch_attend_i8_partial(const LayerView& L, const void* q, int N, int Nq, float sm_scale, const float* logits,
@@ -513,15 +563,21 @@ hipError_t launch_attend_i8_partial(const LayerView& L, const void* q, int N, in
     A.n_chunks = A.n_main + (n_ex + kExtraChunk - 1) / kExtraChunk;
     if (A.n_chunks > A.max_chunks || A.n_chunks < 1) return hipErrorInvalidValue;
     const dim3 grid(A.n_chunks * L.rows + (L.tail_k ? L.rows : 0)), block(kThreads);
-#define SPC_AI8(G_, F_)                                                                                                \
-    do {                                                                                                               \
-        if (keys) SPC_LAUNCH((attend_i8_kernel<G_, F_, true>), grid, block, stream, L, A, sm_scale, keys, key_stride); \
-        else SPC_LAUNCH((attend_i8_kernel<G_, F_, false>), grid, block, stream, L, A, sm_scale, keys, key_stride);     \
+#define SPC_AI8_B(G_, B_, F_)                                                                                              \
+    do {                                                                                                                   \
+        if (keys) SPC_LAUNCH((attend_i8_kernel<G_, B_, F_, true>), grid, block, stream, L, A, sm_scale, keys, key_stride); \
+        else SPC_LAUNCH((attend_i8_kernel<G_, B_, F_, false>), grid, block, stream, L, A, sm_scale, keys, key_stride);     \
+    } while (0)
+#define SPC_AI8(G_, F_)                    \
+    do {                                   \
+        if (L.bits == 2) SPC_AI8_B(G_, 2, F_); \
+        else SPC_AI8_B(G_, 1, F_);         \
     } while (0)
     if (L.group == 32) { if (L.bf16) SPC_AI8(32, true); else SPC_AI8(32, false); }
     else if (L.group == 64) { if (L.bf16) SPC_AI8(64, true); else SPC_AI8(64, false); }
     else if (L.group == 128) { if (L.bf16) SPC_AI8(128, true); else SPC_AI8(128, false); }
     else return hipErrorInvalidValue;
+#undef SPC_AI8_B
 #undef SPC_AI8
     return hipGetLastError();
 }

@@ -327,6 +327,19 @@ def test_unmodified_one_bit_kivi(Hq, Hkv, dtype, g):
         c.check_quantized()
     finally:
         c.close()
+    if Hq == Hkv:
+        # the same form through the call that scores and attends in one launch, the append carried
+        binding.debug_kernel_choice(binding.KEEP_ONE_PASS_LOGITS)
+        c = Case(1, Hq, Hkv, 1300, dtype, 1, g, 48, seed=2600 + g, one_bit_form=1, async_select=2, one_pass=True, fused_append=True)
+        try:
+            c.load()
+            for t in range(40):
+                c.append_token(t)
+                c.decode_step(check_logits=(t % 8 == 0))
+            c.check_quantized()
+        finally:
+            c.close()
+            binding.debug_kernel_choice(0)
     with pytest.raises(binding.SpeCacheError):
         binding.SpeCache(1, 1, 1, 1, 1, 32, 256, 8, synth.FP16, one_bit_form=2)
 
@@ -531,7 +544,11 @@ def test_append_carried_by_the_scoring_launch(Hq, Hkv, dtype, bits, g, R):
     (1, 1, 90, synth.BF16, 2, 32, 64, 16),          # 32 quantised positions: one wave of one chunk, three empty waves
     (2, 2, 5000, synth.FP16, 2, 32, 64, 700),       # index list longer than a wave walks: the workgroup-wide bitmap
     (4, 2, 1500, synth.FP16, 2, 32, 64, 32),        # two query heads per KV head: the two calls one after the other
-    (2, 2, 1500, synth.BF16, 1, 32, 64, 32),        # 1-bit codes: likewise
+    (2, 2, 1500, synth.BF16, 1, 32, 64, 32),        # 1-bit codes: eight channels per code byte, one word per token step
+    (3, 3, 2100, synth.FP16, 1, 64, 128, 300),      # 1 bit, g = 64, workgroup-wide bitmap
+    (2, 2, 1300, synth.BF16, 1, 128, 128, 40),      # 1 bit, g = 128
+    (1, 1, 90, synth.FP16, 1, 32, 64, 16),          # 1 bit, one wave of one chunk
+    (2, 2, 1700, synth.FP16, 4, 32, 64, 48),        # 4-bit codes: the two calls one after the other
 ])
 @pytest.mark.parametrize("carry_append", [False, True])
 def test_scoring_and_attention_in_one_pass(Hq, Hkv, S, dtype, bits, g, R, k, carry_append):

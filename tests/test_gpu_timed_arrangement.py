@@ -30,6 +30,7 @@ SHAPES = {
     "config3": (16, 32, 32, 2048, synth.FP16, 2, 32, 128, 4),
     "config4": (4, 32, 8, 32768, synth.BF16, 2, 64, 512, 4),
     "config5": (1, 32, 8, 131072, synth.BF16, 1, 32, 1024, 4),
+    "M0_1bit_g64": (1, 32, 32, 32768, synth.FP16, 1, 64, 64, 4),    # the 7B shape with 1-bit codes (Eq. 3), g = 64, k = 64
     "M0_4bit": (1, 32, 32, 32768, synth.FP16, 4, 32, 256, 4),       # the 7B shape with 4-bit codes (Eq. 2, B = 4)
     "config4_4bit_g128": (4, 32, 8, 32768, synth.BF16, 4, 128, 512, 2),
 }
