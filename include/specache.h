@@ -245,7 +245,7 @@ int specache_attend(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_r
  * A = Softmax(Q K^T) on the mixed cache and O = A V, with the low-bit logits of both rows computed
  * on the way and the speculative row's selection keys left for the following
  * specache_select_gather (which may be enqueued right after this call: the slot it fills is the
- * other one).  With one query head per KV head, two query rows, 2-bit codes and selection on the
+ * other one).  With one query head per KV head, two query rows, 1- or 2-bit codes and selection on the
  * low-bit logits, one pass over a chunk of 512 positions reads its packed keys, keeps the logits
  * on the chip, and reads its packed values: the logits never travel to memory and back, and the
  * layer-step has one launch less.  Every other shape or option runs the two calls one after the
