@@ -198,6 +198,35 @@ def test_integer_matrix_core_scoring_keeps_fp32_accuracy(dtype, bits, g, spread)
         c.close()
 
 
+@pytest.mark.parametrize("dtype,bits,g,one_pass", [(synth.FP16, 2, 32, False), (synth.BF16, 2, 64, True), (synth.FP16, 1, 32, True),
+                                                    (synth.BF16, 1, 128, False)])
+def test_integer_matrix_core_value_side_with_token_scales_far_apart(dtype, bits, g, one_pass):
+    """One query head per KV head, two rows: the value side of attention runs on the integer matrix cores with p*s as
+    32-bit fixed point relative to the largest value scale of a wave's 128 tokens.  Here the tokens' value
+    magnitudes span 12 binary orders, so a wave mixes scales 4096 apart: a token of small scale and large weight
+    is then held to 2^-18 of its own size.  The output has to stay far inside the 2e-3 bar (measured: 1e-6 to 7e-6)."""
+    from tests.harness import Case
+    if one_pass:
+        binding.debug_kernel_choice(binding.KEEP_ONE_PASS_LOGITS)
+    c = Case(1, 3, 3, 2500, dtype, bits, g, 64, R=max(64, g), seed=4500 + bits * 10 + g,
+             **(dict(async_select=2, one_pass=True) if one_pass else {}))
+    try:
+        rng = np.random.default_rng(11)
+        for h in range(3):
+            scale = np.exp2(rng.integers(0, 13, size=c.v_bits.shape[2])).astype(np.float32)      # per token
+            vf = synth.from_bits(c.v_bits[0, h], dtype) * scale[:, None]
+            c.v_bits[0, h] = synth.to_bits(vf, dtype)
+        c.load()
+        for t in range(3):
+            c.append_token(t)
+            c.decode_step()
+        print(c.stats)
+        assert c.stats["max_out_err"] < 5e-5, c.stats
+    finally:
+        c.close()
+        binding.debug_kernel_choice(0)
+
+
 @pytest.mark.parametrize("bits,g,R", [(2, 32, 64), (1, 64, 128), (2, 128, 128), (4, 32, 64), (4, 128, 256)])
 def test_long_decode_crosses_flushes(bits, g, R):
     """70 decode steps from a short prompt: the residual ring wraps and groups are flushed during decoding
