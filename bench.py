@@ -213,7 +213,7 @@ class Run:
         if not self.spec:
             return "quantize_append, score_topk, gather (main stream), attend"
         if self.calls == "one-pass":
-            return "append_score_attend, select_gather" if self.carry_append else "quantize_append, score_attend, select_gather"
+            return "decode_step (= append_score_attend + select_gather)" if self.carry_append else "quantize_append, score_attend, select_gather"
         if self.async_select == 2:
             return "append_score, select_gather, attend" if self.args.fused_append else "quantize_append, score, select_gather, attend"
         return "quantize_append, score_topk, gather, attend"
@@ -242,9 +242,10 @@ class Run:
                 if not self.carry_append:
                     sc.quantize_append(L, k_p[t], v_p[t], 1, main_h)
                     sc.score_attend(L, q, 2, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h)
-                else:   # the one launch also carries the append of the new pair
-                    sc.append_score_attend(L, k_p[t], v_p[t], q, 2, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h)
-                sc.select_gather(L, ib, (t + 1) % 2 if do_gather else -1, side_h[L % n_side])
+                    sc.select_gather(L, ib, (t + 1) % 2 if do_gather else -1, side_h[L % n_side])
+                else:   # the whole layer-step as one call; its one launch on the main stream also carries the append
+                    sc.decode_step(L, k_p[t], v_p[t], q, self.spec_k_p, self.spec_v_p, slot, self.out_p[L], main_h,
+                                   ib, (t + 1) % 2 if do_gather else -1, side_h[L % n_side])
             else:
                 if self.async_select == 2:
                     if not args.fused_append:

@@ -272,6 +272,20 @@ int specache_append_score_attend(specache_ctx* ctx, int32_t layer, const void* k
                                  void* stream);
 
 /*
+ * One layer-step of Appendix A "Decoding" as ONE call, for the two query rows of a decode step:
+ * specache_append_score_attend(ctx, layer, k_new, v_new, q, 2, k_spec, v_spec, read_slot, out, stream), then
+ * specache_select_gather(ctx, layer, topk_idx_out, fill_slot, side_stream): the new pair is appended, both rows
+ * are scored and attend over the mixed cache (the pairs staged in read_slot in place of their low-bit copies),
+ * and on the side stream K_{t+1} = ArgTopK of the speculative row is selected and its pairs are fetched into
+ * fill_slot for the next step.  Nothing but the two calls: a stepping loop in an interpreted language pays for
+ * one call per layer instead of two.  Arguments, results and errors are those of the two calls (the first
+ * failure is returned and the second call is then not made).
+ */
+int specache_decode_step(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                         const void* k_spec, const void* v_spec, int32_t read_slot, float* out, void* stream,
+                         int32_t* topk_idx_out, int32_t fill_slot, void* side_stream);
+
+/*
  * specache_attend for callers that must not allocate device memory around the call and want
  * the call's scratch out of the context: code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc.  Same arguments, same kernels, same results; the partial

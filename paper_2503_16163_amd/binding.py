@@ -18,7 +18,7 @@ _NAMES = {EINVAL: "EINVAL", ECAPACITY: "ECAPACITY", ENOMEM: "ENOMEM", EHIP: "EHI
 EXPORTS = ["specache_create", "specache_destroy", "specache_last_error", "specache_counts",
            "specache_plan_append", "specache_quantize_append", "specache_score_topk", "specache_gather",
            "specache_score", "specache_select_gather", "specache_append_score",
-           "specache_attend", "specache_score_attend", "specache_append_score_attend", "specache_attend_static", "specache_debug_poison_slot", "specache_debug_fail_alloc", "specache_debug_kernel_choice", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
+           "specache_attend", "specache_score_attend", "specache_append_score_attend", "specache_decode_step", "specache_attend_static", "specache_debug_poison_slot", "specache_debug_fail_alloc", "specache_debug_kernel_choice", "specache_export_quantized", "specache_export_rows", "specache_debug_logits",
            "specache_timing", "specache_measure_hbm_read", "specache_measure_link"]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.specache_attend_static.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
         L.specache_score_attend.argtypes = [vp, i32, vp, i32, vp, vp, i32, vp, vp]
         L.specache_append_score_attend.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, i32, vp, vp]
+        L.specache_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
         L.specache_debug_poison_slot.argtypes = [vp, i32, i32, vp]
         L.specache_debug_kernel_choice.argtypes = [i32]
         L.specache_debug_fail_alloc.argtypes = [i32]
@@ -203,6 +204,11 @@ class SpeCache:
     def append_score_attend(self, layer, k_new, v_new, q, n_rows, k_spec, v_spec, slot, out, stream=None):
         self._check(lib().specache_append_score_attend(self._ctx, layer, _ptr(k_new), _ptr(v_new), _ptr(q), n_rows,
                                                        _ptr(k_spec), _ptr(v_spec), slot, _ptr(out), _stream(stream)))
+
+    def decode_step(self, layer, k_new, v_new, q, k_spec, v_spec, read_slot, out, stream, topk_idx_out, fill_slot, side_stream):
+        self._check(lib().specache_decode_step(self._ctx, layer, _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(k_spec), _ptr(v_spec),
+                                               read_slot, _ptr(out), _stream(stream), _ptr(topk_idx_out), fill_slot,
+                                               _stream(side_stream)))
 
     def attend_static(self, layer, q, n_rows, k_spec, v_spec, slot, out, stream=None):
         self._check(lib().specache_attend_static(self._ctx, layer, _ptr(q), n_rows, _ptr(k_spec), _ptr(v_spec), slot,

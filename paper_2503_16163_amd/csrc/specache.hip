@@ -855,6 +855,13 @@ int specache_append_score_attend(specache_ctx* ctx, int32_t layer, const void* k
     return score_attend_impl(ctx, layer, k_new, v_new, q, n_rows, k_spec, v_spec, slot, out, stream);
 }
 
+int specache_decode_step(specache_ctx* ctx, int32_t layer, const void* k_new, const void* v_new, const void* q,
+                         const void* k_spec, const void* v_spec, int32_t read_slot, float* out, void* stream,
+                         int32_t* topk_idx_out, int32_t fill_slot, void* side_stream) {
+    if (int rc = specache_append_score_attend(ctx, layer, k_new, v_new, q, 2, k_spec, v_spec, read_slot, out, stream)) return rc;
+    return specache_select_gather(ctx, layer, topk_idx_out, fill_slot, side_stream);
+}
+
 int specache_attend_static(specache_ctx* ctx, int32_t layer, const void* q, int32_t n_rows, const void* k_spec,
                            const void* v_spec, int32_t slot, float* out, void* stream) {
     if (!ctx) return SPECACHE_EINVAL;

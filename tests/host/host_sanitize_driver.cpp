@@ -78,6 +78,7 @@ int main() {
     REQUIRE(specache_score(nullptr, 0, nullptr, 2, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_append_score(nullptr, 0, nullptr, nullptr, nullptr, 2, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_select_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);
+    REQUIRE(specache_decode_step(nullptr, 0, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, nullptr, nullptr, 0, nullptr) == SPECACHE_EINVAL);
     REQUIRE(specache_debug_fail_alloc(-1) == SPECACHE_EINVAL);
     REQUIRE(specache_debug_fail_alloc(0) == SPECACHE_OK);
     REQUIRE(specache_gather(nullptr, 0, nullptr, 0, nullptr) == SPECACHE_EINVAL);

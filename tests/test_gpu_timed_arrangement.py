@@ -114,9 +114,8 @@ def run_free_running(name, fused_append=False, poison=False, steps=STEPS, shape=
             slot = (t % 2) if t > 0 else -1
             for L in range(layers):
                 side = sides[L % n_side]
-                if one_pass and fused_append:
-                    sc.append_score_attend(L, nkd, nvd, q, 2, ks, vs, slot, out[L][t], main)
-                    sc.select_gather(L, idx[L][t % 2], (t + 1) % 2, side)
+                if one_pass and fused_append:     # the whole layer-step as one call (= append_score_attend + select_gather)
+                    sc.decode_step(L, nkd, nvd, q, ks, vs, slot, out[L][t], main, idx[L][t % 2], (t + 1) % 2, side)
                 elif one_pass:
                     sc.quantize_append(L, nkd, nvd, 1, main)
                     sc.score_attend(L, q, 2, ks, vs, slot, out[L][t], main)
